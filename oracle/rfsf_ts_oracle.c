@@ -1,0 +1,201 @@
+/*
+ * CPU oracle for the tensor-sketched Random Fourier Signature Features map
+ * (RFSF-TS) and the linear Gram of its features.
+ *
+ * THIS IS TEST INFRASTRUCTURE. It is a plain, slow, fp64 statement of what the
+ * method computes, written from the paper's definitions. It shares no code with
+ * the HIP library, is never called by the product path, and is used only by the
+ * tests, the smoke check and the CPU-baseline leg of the benchmark.
+ *
+ * What is computed (order p = 1, truncation level M), per sequence x_0..x_{L-1}
+ * (L time points, T = L-1 increments), in the paper's order of steps:
+ *
+ *   1. Random Fourier features per level m (Sec. 3.1, eq. (rff); appendix class
+ *      RandomFourierFeatures, W = Z / bandwidth):
+ *        theta = (x_t . W_m[:,a]) / lengthscale
+ *        phi_m(x_t) = F^{-1/2} ( cos(theta_0..F-1) , sin(theta_0..F-1) )   in R^{2F}
+ *      with an independent W_m per level (Sec. 3.2, "independent RFF maps").
+ *   2. Time increments (Sec. 2.1, the difference operator; Sec. 3.2, eq. (rfsf)):
+ *        delta_m[k] = phi_m(x_k) - phi_m(x_{k-1}),  k = 1..T
+ *   3. CountSketch per level (Sec. 3.5, eq. (cs)):
+ *        c_m[k][j] = sum over a with hash_m[a] == j of sign_m[a] * delta_m[k][a]
+ *   4. Level recursion (Sec. 3.5, eq. (ts_rec) with p = 1, convolution form):
+ *        R_1[k] = c_1[k]
+ *        R_m[k] = P_{m-1}[k] (*) c_m[k],   P_{m-1}[k] = sum_{k' < k} R_{m-1}[k']
+ *        Phi_m  = sum_k R_m[k]
+ *      where (*) is circular convolution modulo D (eq. (ts_def)), evaluated
+ *      directly in O(D^2) -- no FFT anywhere in this file.
+ *   5. Output row: ( 1 , Phi_1 , ... , Phi_M ), 1 + M*D numbers (Sec. 1, remark on
+ *      primal features: shape (N, M D + 1); the level-0 term of eq. (ksig finite)
+ *      is the constant 1).
+ *   6. Gram of features: K[i][j] = <PhiX[i], PhiY[j]> (Sec. 1, P_X P_X^T).
+ *
+ * Inputs are the float32 / int32 arrays the GPU library receives, widened to
+ * double on read. OpenMP is used over sequences only (they are independent).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int rfsf_ts_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Steps 1-2 for one sequence: delta[m][k][a], m < M, k < T, a < 2F (k is 0-based:
+ * delta[m][k] = phi_m(x_{k+1}) - phi_m(x_k)). phi is scratch of 2 * 2F doubles. */
+static void increments_one(int64_t L, int d, int M, int F,
+                           const float *x, const float *W, double lengthscale,
+                           double *delta, double *phi)
+{
+    const int64_t T = L - 1;
+    const int twoF = 2 * F;
+    const double scale = 1.0 / sqrt((double)F);
+    for (int m = 0; m < M; ++m) {
+        double *prev = phi, *cur = phi + twoF;
+        for (int64_t t = 0; t < L; ++t) {
+            for (int a = 0; a < F; ++a) {
+                double dot = 0.0;
+                for (int c = 0; c < d; ++c)
+                    dot += (double)x[t * d + c] * (double)W[((int64_t)m * d + c) * F + a];
+                const double theta = dot / lengthscale;
+                cur[a] = scale * cos(theta);
+                cur[F + a] = scale * sin(theta);
+            }
+            if (t > 0) {
+                double *dst = delta + ((int64_t)m * T + (t - 1)) * twoF;
+                for (int a = 0; a < twoF; ++a)
+                    dst[a] = cur[a] - prev[a];
+            }
+            double *tmp = prev; prev = cur; cur = tmp;
+        }
+    }
+}
+
+/* delta[N][T][M][2F] (double) -- steps 1-2 only, for stage-wise checks. */
+int rfsf_ts_oracle_increments(int64_t N, int64_t L, int d, int M, int F,
+                              const float *X, const float *W, double lengthscale,
+                              double *dphi)
+{
+    if (N < 0 || L < 1 || d < 1 || M < 1 || F < 1 || !(lengthscale > 0.0)) return -1;
+    const int64_t T = L - 1;
+    const int twoF = 2 * F;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t n = 0; n < N; ++n) {
+        double *delta = (double *)malloc(sizeof(double) * (size_t)(M * (T > 0 ? T : 1)) * twoF);
+        double *phi = (double *)malloc(sizeof(double) * 2 * twoF);
+        if (!delta || !phi) {
+#pragma omp atomic write
+            fail = 1;
+            free(delta); free(phi); continue;
+        }
+        increments_one(L, d, M, F, X + n * L * d, W, lengthscale, delta, phi);
+        for (int64_t k = 0; k < T; ++k)
+            for (int m = 0; m < M; ++m)
+                memcpy(dphi + ((n * T + k) * M + m) * twoF,
+                       delta + ((int64_t)m * T + k) * twoF, sizeof(double) * twoF);
+        free(delta); free(phi);
+    }
+    return fail ? -2 : 0;
+}
+
+/* out[N][ld_out] (double), columns 0 .. M*D written. */
+int rfsf_ts_oracle_features(int64_t N, int64_t L, int d, int M, int F, int D,
+                            const float *X, const float *W,
+                            const int32_t *hash, const float *sign,
+                            double lengthscale, double *out, int64_t ld_out)
+{
+    if (N < 0 || L < 1 || d < 1 || M < 1 || F < 1 || D < 1) return -1;
+    if (!(lengthscale > 0.0) || ld_out < 1 + (int64_t)M * D) return -1;
+    const int64_t T = L - 1;
+    const int twoF = 2 * F;
+    for (int64_t i = 0; i < (int64_t)M * twoF; ++i)
+        if (hash[i] < 0 || hash[i] >= D) return -3;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t n = 0; n < N; ++n) {
+        double *row = out + n * ld_out;
+        row[0] = 1.0;                                   /* level 0 */
+        for (int64_t j = 0; j < (int64_t)M * D; ++j) row[1 + j] = 0.0;
+        if (T == 0) continue;                           /* no increments: empty sums */
+
+        double *delta = (double *)malloc(sizeof(double) * (size_t)M * T * twoF);
+        double *phi = (double *)malloc(sizeof(double) * 2 * twoF);
+        double *c = (double *)calloc((size_t)M * T * D, sizeof(double));
+        double *Rprev = (double *)malloc(sizeof(double) * (size_t)T * D);
+        double *Rcur = (double *)malloc(sizeof(double) * (size_t)T * D);
+        double *P = (double *)malloc(sizeof(double) * D);
+        if (!delta || !phi || !c || !Rprev || !Rcur || !P) {
+#pragma omp atomic write
+            fail = 1;
+            free(delta); free(phi); free(c); free(Rprev); free(Rcur); free(P);
+            continue;
+        }
+        /* steps 1-2 */
+        increments_one(L, d, M, F, X + n * L * d, W, lengthscale, delta, phi);
+        /* step 3: CountSketch of every increment with the level's own hash/sign */
+        for (int m = 0; m < M; ++m)
+            for (int64_t k = 0; k < T; ++k) {
+                const double *dl = delta + ((int64_t)m * T + k) * twoF;
+                double *ck = c + ((int64_t)m * T + k) * D;
+                for (int a = 0; a < twoF; ++a)
+                    ck[hash[m * twoF + a]] += (double)sign[m * twoF + a] * dl[a];
+            }
+        /* step 4: level 1 */
+        memcpy(Rprev, c, sizeof(double) * (size_t)T * D);
+        for (int64_t k = 0; k < T; ++k)
+            for (int j = 0; j < D; ++j)
+                row[1 + j] += Rprev[k * D + j];
+        /* step 4: levels 2..M */
+        for (int m = 1; m < M; ++m) {
+            for (int j = 0; j < D; ++j) P[j] = 0.0;     /* exclusive prefix of level m-1 */
+            for (int64_t k = 0; k < T; ++k) {
+                const double *ck = c + ((int64_t)m * T + k) * D;
+                double *r = Rcur + k * D;
+                for (int j = 0; j < D; ++j) {
+                    double acc = 0.0;
+                    for (int q = 0; q < D; ++q) {
+                        int idx = j - q;
+                        if (idx < 0) idx += D;
+                        acc += P[q] * ck[idx];
+                    }
+                    r[j] = acc;
+                }
+                for (int j = 0; j < D; ++j) P[j] += Rprev[k * D + j];   /* after use */
+            }
+            double *blk = row + 1 + (int64_t)m * D;
+            for (int64_t k = 0; k < T; ++k)
+                for (int j = 0; j < D; ++j)
+                    blk[j] += Rcur[k * D + j];
+            double *tmp = Rprev; Rprev = Rcur; Rcur = tmp;
+        }
+        free(delta); free(phi); free(c); free(Rprev); free(Rcur); free(P);
+    }
+    return fail ? -2 : 0;
+}
+
+/* K[Nx][ldk] = PhiX[Nx][ldx] . PhiY[Ny][ldy]^T over the first ncols columns. */
+int rfsf_ts_oracle_gram(const double *PhiX, int64_t Nx, int64_t ldx,
+                        const double *PhiY, int64_t Ny, int64_t ldy,
+                        int64_t ncols, double *K, int64_t ldk)
+{
+    if (Nx < 0 || Ny < 0 || ncols < 0 || ldx < ncols || ldy < ncols || ldk < Ny) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < Nx; ++i)
+        for (int64_t j = 0; j < Ny; ++j) {
+            double acc = 0.0;
+            for (int64_t c = 0; c < ncols; ++c)
+                acc += PhiX[i * ldx + c] * PhiY[j * ldy + c];
+            K[i * ldk + j] = acc;
+        }
+    return 0;
+}

@@ -1,0 +1,113 @@
+"""ctypes loader for the fp64 CPU oracle in rfsf_ts_oracle.c.
+
+Test infrastructure only: imported by tests/, the smoke check and the
+CPU-baseline leg of the benchmark. The product path never imports this.
+The C file states what is computed and cites the paper passage for each step;
+this file only builds it with gcc, marshals numpy arrays and checks shapes.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rfsf_ts_oracle.c")
+_LIB = os.path.join(_HERE, "librfsf_ts_oracle.so")
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP over sequences, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c99", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            build(force=True)
+        lib = ctypes.CDLL(_LIB)
+        i64, i32, dbl = ctypes.c_int64, ctypes.c_int, ctypes.c_double
+        vp = ctypes.c_void_p
+        lib.rfsf_ts_oracle_threads.restype = ctypes.c_int
+        lib.rfsf_ts_oracle_features.restype = ctypes.c_int
+        lib.rfsf_ts_oracle_features.argtypes = [i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, dbl, vp, i64]
+        lib.rfsf_ts_oracle_increments.restype = ctypes.c_int
+        lib.rfsf_ts_oracle_increments.argtypes = [i64, i64, i32, i32, i32, vp, vp, dbl, vp]
+        lib.rfsf_ts_oracle_gram.restype = ctypes.c_int
+        lib.rfsf_ts_oracle_gram.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, i64]
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    return int(_load().rfsf_ts_oracle_threads())
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _check_inputs(X, W, hash_, sign):
+    X, W, sign = _f32(X), _f32(W), _f32(sign)
+    hash_ = np.ascontiguousarray(hash_, dtype=np.int32)
+    if X.ndim != 3 or W.ndim != 3 or hash_.ndim != 2 or sign.shape != hash_.shape:
+        raise ValueError("expected X[N,L,d], W[M,d,F], hash[M,2F], sign[M,2F]")
+    N, L, d = X.shape
+    M, d2, F = W.shape
+    if d2 != d or hash_.shape != (M, 2 * F):
+        raise ValueError("inconsistent shapes")
+    return X, W, hash_, sign, N, L, d, M, F
+
+
+def features(X, W, hash_, sign, lengthscale: float, D: int) -> np.ndarray:
+    """float64 [N, 1 + M*D]: column 0 is level 0 (= 1), then M blocks of D."""
+    X, W, hash_, sign, N, L, d, M, F = _check_inputs(X, W, hash_, sign)
+    out = np.empty((N, 1 + M * D), dtype=np.float64)
+    rc = _load().rfsf_ts_oracle_features(N, L, d, M, F, int(D), X.ctypes.data, W.ctypes.data,
+                                         hash_.ctypes.data, sign.ctypes.data, float(lengthscale),
+                                         out.ctypes.data, out.shape[1])
+    if rc != 0:
+        raise RuntimeError(f"rfsf_ts_oracle_features failed with code {rc}")
+    return out
+
+
+def increments(X, W, lengthscale: float) -> np.ndarray:
+    """float64 [N, T, M, 2F]: time increments of the per-level random Fourier features."""
+    X, W = _f32(X), _f32(W)
+    N, L, d = X.shape
+    M, d2, F = W.shape
+    if d2 != d:
+        raise ValueError("inconsistent shapes")
+    out = np.empty((N, L - 1, M, 2 * F), dtype=np.float64)
+    rc = _load().rfsf_ts_oracle_increments(N, L, d, M, F, X.ctypes.data, W.ctypes.data,
+                                           float(lengthscale), out.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"rfsf_ts_oracle_increments failed with code {rc}")
+    return out
+
+
+def gram(PhiX, PhiY=None) -> np.ndarray:
+    """float64 [Nx, Ny] = PhiX PhiY^T by three explicit loops."""
+    PhiX = np.ascontiguousarray(PhiX, dtype=np.float64)
+    PhiY = PhiX if PhiY is None else np.ascontiguousarray(PhiY, dtype=np.float64)
+    if PhiX.ndim != 2 or PhiY.ndim != 2 or PhiX.shape[1] != PhiY.shape[1]:
+        raise ValueError("expected PhiX[Nx,C], PhiY[Ny,C]")
+    K = np.empty((PhiX.shape[0], PhiY.shape[0]), dtype=np.float64)
+    rc = _load().rfsf_ts_oracle_gram(PhiX.ctypes.data, PhiX.shape[0], PhiX.shape[1],
+                                     PhiY.ctypes.data, PhiY.shape[0], PhiY.shape[1],
+                                     PhiX.shape[1], K.ctypes.data, K.shape[1])
+    if rc != 0:
+        raise RuntimeError(f"rfsf_ts_oracle_gram failed with code {rc}")
+    return K

@@ -1,0 +1,260 @@
+"""CPU pins of the fp64 oracle: each test fixes the oracle against something other
+than itself (closed forms, brute force over the definition, invariants, special
+cases, a library routine, the exact kernel within a statistical bound)."""
+import math
+
+import numpy as np
+import pytest
+
+from tests import pins
+
+
+def _tables(rng, M, F, D):
+    hash_ = rng.integers(0, D, size=(M, 2 * F)).astype(np.int32)
+    sign = (2.0 * rng.integers(0, 2, size=(M, 2 * F)) - 1.0).astype(np.float32)
+    return hash_, sign
+
+
+def _case(seed, N, L, d, M, F, D, ls=1.3):
+    rng = np.random.default_rng(seed)
+    X = np.cumsum(rng.standard_normal((N, L, d)) * 0.4, axis=1).astype(np.float32)
+    W = rng.standard_normal((M, d, F)).astype(np.float32)
+    hash_, sign = _tables(rng, M, F, D)
+    return X, W, hash_, sign, float(np.float32(ls))
+
+
+# ---------------------------------------------------------------- stage 1-2: RFF and increments
+def test_rff_single_frequency_closed_form(oracle):
+    """Sec. 3.1 eq. (rff): with one non-zero entry W[m, c0, a0] = w the only moving
+    coordinates are cos/sin of x[c0] * w / l at positions a0 and F + a0; every other
+    cos coordinate is the constant F^{-1/2} and every other sin coordinate is 0. Pins
+    the [M, d, F] indexing, the division by the lengthscale, the cos-then-sin order
+    and the F^{-1/2} scale."""
+    N, L, d, M, F = 2, 5, 3, 2, 4
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((N, L, d)).astype(np.float32)
+    for (m0, c0, a0) in [(0, 2, 1), (1, 0, 3)]:
+        W = np.zeros((M, d, F), dtype=np.float32)
+        W[m0, c0, a0] = 0.75
+        ls = 2.0
+        got = oracle.increments(X, W, ls)                       # [N, T, M, 2F]
+        th = X[:, :, c0].astype(np.float64) * 0.75 / ls
+        want = np.zeros((N, L - 1, M, 2 * F))
+        want[:, :, m0, a0] = (np.cos(th[:, 1:]) - np.cos(th[:, :-1])) / math.sqrt(F)
+        want[:, :, m0, F + a0] = (np.sin(th[:, 1:]) - np.sin(th[:, :-1])) / math.sqrt(F)
+        np.testing.assert_allclose(got, want, atol=1e-15)
+
+
+def test_rff_kernel_identity(oracle):
+    """<phi(x), phi(y)> = (1/F) sum_a cos(w_a . (x - y) / l) and |phi(x)|^2 = 1, so a
+    two-point 'sequence' (x, y) has |delta|^2 = 2 - 2 <phi(x), phi(y)> (eq. (rff))."""
+    rng = np.random.default_rng(2)
+    d, F, ls = 4, 16, 1.7
+    x, y = rng.standard_normal(d), rng.standard_normal(d)
+    X = np.stack([x, y])[None].astype(np.float32)
+    W = rng.standard_normal((1, d, F)).astype(np.float32)
+    delta = oracle.increments(X, W, ls)[0, 0, 0]
+    xy = (X[0, 0].astype(np.float64) - X[0, 1].astype(np.float64))
+    kern = np.mean(np.cos(xy @ W[0].astype(np.float64) / ls))
+    assert abs(delta @ delta - (2.0 - 2.0 * kern)) < 1e-14
+
+
+def test_increments_match_numpy(oracle):
+    X, W, _, _, ls = _case(3, N=3, L=7, d=5, M=3, F=6, D=8)
+    np.testing.assert_allclose(oracle.increments(X, W, ls), pins.rff_increments_numpy(X, W, ls),
+                               rtol=0, atol=1e-14)
+
+
+# ---------------------------------------------------------------- the closed definition, brute force
+@pytest.mark.parametrize("T,F,M,D", [(6, 2, 3, 4), (5, 1, 3, 2), (4, 2, 2, 8), (6, 2, 3, 8), (3, 2, 3, 4)])
+def test_bruteforce_tuples(oracle, T, F, M, D):
+    """Sec. 3.5 eq. (ts), p = 1: explicit sum over i_1 < ... < i_m of the sketched
+    tensor product, coordinate by coordinate."""
+    X, W, hash_, sign, ls = _case(10 + T + D, N=2, L=T + 1, d=2, M=M, F=F, D=D)
+    got = oracle.features(X, W, hash_, sign, ls, D)
+    delta = oracle.increments(X, W, ls)
+    assert np.all(got[:, 0] == 1.0)
+    for n in range(X.shape[0]):
+        want = pins.brute_force_tensor_sketch(delta[n], hash_, sign, D)
+        np.testing.assert_allclose(got[n, 1:].reshape(M, D), want, rtol=0, atol=1e-13)
+
+
+def test_bruteforce_tuples_numpy_increments(oracle):
+    """Same as above, but the increments come from the numpy formula, so the whole
+    oracle (stages 1-5) is compared with an implementation that shares nothing."""
+    T, F, M, D = 5, 2, 3, 4
+    X, W, hash_, sign, ls = _case(77, N=1, L=T + 1, d=3, M=M, F=F, D=D)
+    delta = pins.rff_increments_numpy(X, W, ls)
+    want = pins.brute_force_tensor_sketch(delta[0], hash_, sign, D)
+    got = oracle.features(X, W, hash_, sign, ls, D)
+    np.testing.assert_allclose(got[0, 1:].reshape(M, D), want, rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------- invariants
+def test_level1_telescopes(oracle):
+    """Linearity of the count sketch (eq. (cs)): Phi_1 = CS_1(phi_1(x_last) - phi_1(x_first))."""
+    X, W, hash_, sign, ls = _case(4, N=5, L=23, d=3, M=2, F=8, D=16)
+    got = oracle.features(X, W, hash_, sign, ls, 16)
+    F = 8
+    th0 = X[:, 0].astype(np.float64) @ W[0].astype(np.float64) / ls
+    th1 = X[:, -1].astype(np.float64) @ W[0].astype(np.float64) / ls
+    v = np.concatenate([np.cos(th1) - np.cos(th0), np.sin(th1) - np.sin(th0)], axis=1) / math.sqrt(F)
+    want = np.zeros((5, 16))
+    for a in range(2 * F):
+        want[:, hash_[0, a]] += sign[0, a] * v[:, a]
+    np.testing.assert_allclose(got[:, 1:17], want, rtol=0, atol=1e-14)
+
+
+def test_dc_and_nyquist_bins(oracle):
+    """Summing a level block over buckets removes the hash: with u_k[t] = sum_a
+    sign_k[a] delta_k[t][a], sum_j Phi_m[j] = sum_{i_1<...<i_m} prod_k u_k[i_k]; with
+    v_k[t] = sum_a (-1)^{hash_k[a]} sign_k[a] delta_k[t][a] the alternating sum gives
+    the same for v (bucket index adds under convolution)."""
+    X, W, hash_, sign, ls = _case(5, N=4, L=30, d=3, M=4, F=8, D=16)
+    got = oracle.features(X, W, hash_, sign, ls, 16)[:, 1:].reshape(4, 4, 16)
+    delta = pins.rff_increments_numpy(X, W, ls)                 # [N, T, M, 2F]
+    alt = (-1.0) ** np.arange(16)
+    for weights, red in ((np.ones_like(sign, dtype=np.float64), np.ones(16)),
+                         ((-1.0) ** hash_.astype(np.float64), alt)):
+        u = np.einsum("ntma,ma->ntm", delta, sign * weights)
+        N, T, M = u.shape
+        e = np.zeros((N, M + 1))
+        e[:, 0] = 1.0
+        for t in range(T):                                      # elementary-symmetric-like DP
+            for m in range(M, 0, -1):
+                e[:, m] += e[:, m - 1] * u[:, t, m - 1]
+        np.testing.assert_allclose(got @ red, e[:, 1:], rtol=0, atol=1e-13)
+
+
+def test_repeated_time_point_changes_nothing(oracle):
+    """A repeated point adds a zero increment; every sum over tuples ignores it."""
+    X, W, hash_, sign, ls = _case(6, N=3, L=9, d=2, M=3, F=4, D=8)
+    Xr = np.concatenate([X[:, :4], X[:, 3:4], X[:, 4:]], axis=1)
+    np.testing.assert_allclose(oracle.features(Xr, W, hash_, sign, ls, 8),
+                               oracle.features(X, W, hash_, sign, ls, 8), rtol=0, atol=1e-14)
+
+
+def test_short_sequences(oracle):
+    """Empty sums: L = 1 gives (1, 0, ..); level m vanishes when m > T."""
+    X, W, hash_, sign, ls = _case(7, N=2, L=3, d=2, M=4, F=4, D=8)
+    one = oracle.features(X[:, :1], W, hash_, sign, ls, 8)
+    assert np.all(one[:, 0] == 1.0) and np.all(one[:, 1:] == 0.0)
+    two = oracle.features(X[:, :2], W, hash_, sign, ls, 8)      # T = 1
+    assert np.any(two[:, 1:9] != 0.0) and np.all(two[:, 9:] == 0.0)
+    three = oracle.features(X, W, hash_, sign, ls, 8)           # T = 2
+    assert np.any(three[:, 9:17] != 0.0) and np.all(three[:, 17:] == 0.0)
+
+
+def test_constant_hash_collapses_to_bucket_zero(oracle):
+    X, W, hash_, sign, ls = _case(8, N=2, L=12, d=2, M=3, F=4, D=8)
+    h0 = np.zeros_like(hash_)
+    got = oracle.features(X, W, h0, sign, ls, 8)[:, 1:].reshape(2, 3, 8)
+    ref = oracle.features(X, W, hash_, sign, ls, 8)[:, 1:].reshape(2, 3, 8)
+    assert np.all(got[:, :, 1:] == 0.0)
+    np.testing.assert_allclose(got[:, :, 0], ref.sum(axis=2), rtol=0, atol=1e-13)
+
+
+def test_injective_hash_gives_unsketched_coordinates(oracle):
+    """With D large and hash_k[a] = a * (2F)^k the bucket index encodes the tensor
+    coordinate uniquely, so level 2 holds the unprojected signature features
+    sum_{i<j} delta_1[i][a] delta_2[j][b] (Sec. 3.2, eq. (rfsf)) at bucket a + 2F b."""
+    F, M, D = 2, 2, 16
+    X, W, _, _, ls = _case(9, N=1, L=8, d=2, M=M, F=F, D=D)
+    hash_ = np.stack([np.arange(4), 4 * np.arange(4)]).astype(np.int32)
+    sign = np.ones((M, 4), dtype=np.float32)
+    got = oracle.features(X, W, hash_, sign, ls, D)[0, 1:].reshape(M, D)
+    delta = pins.rff_increments_numpy(X, W, ls)[0]              # [T, M, 2F]
+    T = delta.shape[0]
+    want = np.zeros((4, 4))
+    for i in range(T):
+        for j in range(i + 1, T):
+            want += np.outer(delta[i, 0], delta[j, 1])
+    np.testing.assert_allclose(got[1].reshape(4, 4).T, want, rtol=0, atol=1e-14)
+
+
+# ---------------------------------------------------------------- the FFT route (library routine)
+@pytest.mark.parametrize("D", [8, 32, 6])
+def test_matches_library_fft_route(oracle, D):
+    """Sec. 3.5 eq. (ts_rec), second line: the same features through numpy's real FFT
+    and the per-bin streaming recurrence. D = 6 shows the oracle does not need a power
+    of two."""
+    X, W, hash_, sign, ls = _case(20 + D, N=3, L=17, d=3, M=4, F=5, D=D)
+    got = oracle.features(X, W, hash_, sign, ls, D)
+    delta = oracle.increments(X, W, ls)
+    for n in range(3):
+        want = pins.streaming_frequency_domain(delta[n], hash_, sign, D)
+        np.testing.assert_allclose(got[n, 1:].reshape(4, D), want, rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- statistics: unbiased for the signature kernel
+def test_sigkernel_dp_matches_its_definition():
+    """The dynamic programme used as the exact reference equals eq. (sigkernelm), p = 1."""
+    rng = np.random.default_rng(11)
+    x = np.cumsum(rng.standard_normal((5, 2)) * 0.5, axis=0)
+    y = np.cumsum(rng.standard_normal((6, 2)) * 0.5, axis=0)
+    np.testing.assert_allclose(pins.truncated_sigkernel_levels(x, y, 1.1, 3),
+                               pins.truncated_sigkernel_levels_bruteforce(x, y, 1.1, 3),
+                               rtol=1e-12, atol=1e-14)
+
+
+def test_unbiased_for_truncated_signature_kernel(oracle):
+    """E <Phi_m(x), Phi_m(y)> = k_m(x, y) level by level (unbiasedness of RFF, of RFSF and
+    of the count / tensor sketch, Secs. 3.1, 3.2, 3.5). S independent table draws;
+    tolerance |mean - k_m| <= 4 SE for every level and every pair, SE = std / sqrt(S);
+    and SE shrinks like S^{-1/2}."""
+    L, d, F, D, M, ls = 8, 2, 16, 32, 3, 1.0
+    rng = np.random.default_rng(12)
+    X = np.cumsum(rng.standard_normal((2, L, d)) * 0.6, axis=1).astype(np.float32)
+    S = 2000
+    prods = np.zeros((S, 3, M))                                  # pairs (x,x), (x,y), (y,y)
+    for s in range(S):
+        r = np.random.default_rng([13, s])
+        W = r.standard_normal((M, d, F)).astype(np.float32)
+        hash_, sign = _tables(r, M, F, D)
+        P = oracle.features(X, W, hash_, sign, ls, D)[:, 1:].reshape(2, M, D)
+        prods[s, 0] = np.einsum("md,md->m", P[0], P[0])
+        prods[s, 1] = np.einsum("md,md->m", P[0], P[1])
+        prods[s, 2] = np.einsum("md,md->m", P[1], P[1])
+    Xd = X.astype(np.float64)
+    exact = np.stack([pins.truncated_sigkernel_levels(Xd[0], Xd[0], ls, M),
+                      pins.truncated_sigkernel_levels(Xd[0], Xd[1], ls, M),
+                      pins.truncated_sigkernel_levels(Xd[1], Xd[1], ls, M)])
+    mean = prods.mean(axis=0)
+    se = prods.std(axis=0, ddof=1) / math.sqrt(S)
+    assert np.all(np.abs(mean - exact) <= 4.0 * se), (mean, exact, se)
+    assert np.all(exact[[0, 2]] > 10.0 * se[[0, 2]])             # the diagonal pairs have power
+    se_quarter = prods[: S // 4].std(axis=0, ddof=1) / math.sqrt(S // 4)
+    ratio = se_quarter / se
+    assert np.all((ratio > 1.5) & (ratio < 2.6)), ratio
+
+
+# ---------------------------------------------------------------- Gram
+def test_gram_properties(oracle):
+    rng = np.random.default_rng(14)
+    A = rng.standard_normal((7, 13))
+    B = rng.standard_normal((5, 13))
+    K = oracle.gram(A, B)
+    np.testing.assert_allclose(K, A @ B.T, rtol=1e-13, atol=1e-13)
+    Kaa = oracle.gram(A)
+    assert np.array_equal(Kaa, Kaa.T)
+    np.testing.assert_allclose(np.diag(Kaa), np.sum(A * A, axis=1), rtol=1e-14)
+    assert np.linalg.eigvalsh(Kaa).min() > -1e-12
+
+
+def test_gram_of_features_is_kernel_estimate(oracle):
+    """K = P_X P_X^T including the level-0 column: K[i,j] = 1 + sum_m <Phi_m(x_i), Phi_m(x_j)>."""
+    X, W, hash_, sign, ls = _case(15, N=4, L=6, d=2, M=2, F=4, D=8)
+    P = oracle.features(X, W, hash_, sign, ls, 8)
+    K = oracle.gram(P)
+    blocks = P[:, 1:].reshape(4, 2, 8)
+    np.testing.assert_allclose(K, 1.0 + np.einsum("imd,jmd->ij", blocks, blocks), rtol=1e-13)
+
+
+def test_rejects_bad_arguments(oracle):
+    X, W, hash_, sign, ls = _case(16, N=1, L=4, d=2, M=2, F=2, D=4)
+    bad = hash_.copy()
+    bad[0, 0] = 4
+    with pytest.raises(RuntimeError):
+        oracle.features(X, W, bad, sign, ls, 4)
+    with pytest.raises(RuntimeError):
+        oracle.features(X, W, hash_, sign, 0.0, 4)
