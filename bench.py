@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the RFSF-TS hot path on one MI355X.
+
+One "step" = one pass of the whole path over one synthetic batch that is already resident in
+HBM: random Fourier features, time increments, CountSketch, FFT-domain level recursion
+(rfsf_ts_features) and the linear Gram of the resulting features (rfsf_ts_gram). For the
+workload with a second batch, the step also computes the second batch's features and the
+Gram is the cross Gram. The metric is sequences x time points per second, (N [+ N2]) * L / t_step.
+
+Prints ONE JSON line. Besides the required fields it carries
+  "roofline"     for the kernel that takes most of the step (algorithmic bytes or flops per
+                 launch / average launch duration measured with HIP events on the launch stream),
+  "kernels"      the same figures for all three kernels,
+  "cpu_baseline" the fp64 CPU oracle timed on this machine's host cores on a bounded sample,
+  "parity"       block / Gram errors of the GPU result against that oracle sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+MFMA_FP32_PEAK_TFLOPS = 157.3    # MI355X dense fp32 matrix, published
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="small", choices=["tiny", "small", "medium", "long", "large"])
+    ap.add_argument("--cpu-rows", type=int, default=-1, help="oracle sample size (-1: per-workload default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (sequences are independent; sharding N over "
+              "GPUs is design-only). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2501_07145_amd as rfsf
+    from paper_2501_07145_amd import workloads as wl
+
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+    inp = wl.make_inputs(w, 0)
+    dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items() if isinstance(v, np.ndarray)}
+    ls = inp["lengthscale"]
+    X2 = torch.from_numpy(wl.make_paths(w.scaled(N=w.N2), 1)).cuda() if w.N2 else None
+
+    rec_bytes, _ = rfsf.rfsf_ts_workspace_bytes(w.N, w.L, w.d, w.M, w.F, w.D, w.rff_bf16)
+    workspace = torch.empty(rec_bytes, dtype=torch.uint8, device="cuda")
+    ld = rfsf.feature_row_stride(w.M, w.D)
+    out = torch.empty((w.N, ld), dtype=torch.float32, device="cuda")[:, :w.ncols]
+    out2 = torch.empty((w.N2, ld), dtype=torch.float32, device="cuda")[:, :w.ncols] if w.N2 else None
+    K = torch.empty((w.N, w.N2 if w.N2 else w.N), dtype=torch.float32, device="cuda")
+
+    def step():
+        rfsf.rfsf_ts_features(dev["X"], dev["W"], dev["hash"], dev["sign"], ls, w.D, out=out,
+                              workspace=workspace, rff_bf16=w.rff_bf16)
+        if X2 is not None:
+            rfsf.rfsf_ts_features(X2, dev["W"], dev["hash"], dev["sign"], ls, w.D, out=out2,
+                                  workspace=workspace, rff_bf16=w.rff_bf16)
+            rfsf.rfsf_ts_gram(out, out2, K=K)
+        else:
+            rfsf.rfsf_ts_gram(out, K=K)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / args.steps
+
+    # same K steps again with per-kernel HIP events on the launch stream
+    rfsf.rfsf_ts_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = rfsf.rfsf_ts_profile_read(reset=True)
+    rfsf.rfsf_ts_profile_enable(False)
+
+    units = (w.N + w.N2) * w.L                       # sequence-steps per step
+    incr_bytes_per_unit = 4.0 * w.M * 2 * w.F          # fp32 increments written by one kernel, read by the next
+    n_seq = w.N + w.N2
+    kernels = {}
+
+    def entry(name, bound, work_per_step, unit, peak):
+        n = prof[f"launches_{name}"]
+        if n == 0:
+            return
+        avg_ms = prof[f"ms_{name}"] / n
+        per_launch = work_per_step * args.steps / n
+        achieved = per_launch / (avg_ms * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+        kernels[name] = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+                         "frac": achieved / peak, "traffic": None, "avg_launch_ms": avg_ms,
+                         "launches_per_step": n / args.steps, "ms_per_step": prof[f"ms_{name}"] / args.steps}
+
+    entry("rff_increments", "hbm", units * (4.0 * w.d + incr_bytes_per_unit), "GB/s", HBM_PEAK_GBS)
+    entry("sketch_fft_scan", "hbm", units * incr_bytes_per_unit + 4.0 * n_seq * w.M * w.D, "GB/s", HBM_PEAK_GBS)
+    Ny = w.N2 if w.N2 else w.N
+    entry("gram", "mfma", 2.0 * w.N * Ny * w.ncols, "TFLOP/s", MFMA_FP32_PEAK_TFLOPS)
+    dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    roofline = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
+    roofline["kernel"] = dominant
+
+    result = {
+        "metric": "rfsf_ts_sequence_steps_per_s",
+        "value": units / t_step,
+        "unit": "sequences*steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": t_step * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16+f32" if w.rff_bf16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "N": w.N, "N2": w.N2, "L": w.L, "d": w.d, "M": w.M, "F": w.F, "D": w.D,
+                   "lengthscale": ls, "paths": w.kind, "rff_bf16": w.rff_bf16,
+                   "step": "features + Gram", "workspace_bytes": rec_bytes},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        from tests.parity import block_errors, gram_error
+        default_rows = {"tiny": 16, "small": 1000, "medium": 32, "long": 16, "large": 32}[w.name]
+        rows = min(w.N, default_rows if args.cpu_rows < 0 else args.cpu_rows)
+        sel = np.linspace(0, w.N - 1, rows).round().astype(np.int64)
+        Xs = inp["X"][sel]
+        Wo = wl.round_to_bf16(inp["W"]) if w.rff_bf16 else inp["W"]   # the rounding the bf16 variant applies
+        t0 = time.perf_counter()
+        want = oracle.features(Xs, Wo, inp["hash"], inp["sign"], ls, w.D)
+        t_feat = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        Kw = oracle.gram(want)
+        t_gram = time.perf_counter() - t0
+        got = out.cpu().numpy()[sel]
+        err = block_errors(got, want, w.M, w.D)
+        Ksel = (rfsf.rfsf_ts_gram(out[torch.from_numpy(sel).cuda()].contiguous()) if X2 is not None
+                else K[torch.from_numpy(sel).cuda()][:, torch.from_numpy(sel).cuda()])
+        torch.cuda.synchronize()
+        result["cpu_baseline"] = {
+            "value": rows * w.L / (t_feat + t_gram), "unit": "sequences*steps/s", "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": f"{rows} of {w.N} sequences (evenly spaced rows), features {t_feat:.2f} s + "
+                      f"{rows}x{rows} Gram {t_gram:.2f} s, fp64, direct O(D^2) convolution",
+        }
+        result["parity"] = {"rows": int(rows), "max_block_err_per_level": [float(e) for e in err],
+                            "gram_err": gram_error(Ksel.cpu().numpy(), Kw)}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

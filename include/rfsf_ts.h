@@ -1,0 +1,146 @@
+/*
+ * rfsf_ts.h -- C ABI of the MI355X (gfx950) library for tensor-sketched Random
+ * Fourier Signature Features (RFSF-TS, order p = 1) and the linear Gram of the
+ * features.
+ *
+ * Symbols used throughout (the paper's own letters in brackets):
+ *   N  sequences                      L  time points per sequence, T = L-1 increments
+ *   d  state dimension                M  truncation level
+ *   F  random Fourier frequencies per level [paper: D]; the static features have 2F dims
+ *   D  count-sketch buckets per level [paper: Q]; must be a power of two here
+ *
+ * General rules for every entry point
+ *   - Every data pointer is a DEVICE pointer on the current HIP device, owned by
+ *     the caller. The library never frees or keeps caller memory and allocates
+ *     nothing that the caller sees.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream). The calls do not synchronise the device; results are
+ *     ready when the stream has drained.
+ *   - Return value: RFSF_OK (0) or a negative RFSF_E_* code. After an argument
+ *     error nothing has been enqueued and no output byte has been written.
+ */
+#ifndef RFSF_TS_H
+#define RFSF_TS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    RFSF_OK = 0,
+    RFSF_E_NULLPTR = -1,            /* a required pointer is NULL                         */
+    RFSF_E_BAD_SHAPE = -2,          /* N < 0, L < 1, d < 1, M < 1, F < 1 or size overflow */
+    RFSF_E_D_NOT_POW2 = -3,         /* D is not a power of two in [2, 4096]               */
+    RFSF_E_BAD_STRIDE = -4,         /* a leading dimension is smaller than the row        */
+    RFSF_E_BAD_LENGTHSCALE = -5,    /* lengthscale is not a finite number > 0             */
+    RFSF_E_WORKSPACE_TOO_SMALL = -6,/* workspace cannot hold one chunk (see below)        */
+    RFSF_E_HIP = -7,                /* a HIP runtime call or kernel launch failed         */
+    RFSF_E_BAD_TABLE = -8,          /* hash outside [0, D) or sign not +-1 (validate)     */
+    RFSF_E_UNSUPPORTED = -9         /* valid but outside what the kernels cover           */
+};
+
+typedef struct {
+    int64_t N, L;        /* sequences, time points (L >= 1)                                */
+    int32_t d, M, F, D;  /* state dim, levels, frequencies per level, buckets per level    */
+    int64_t ld_out;      /* row stride of `out` in floats, >= 1 + M*D                      */
+    int32_t rff_bf16;    /* 0: fp32 projection. 1: W rounded to bf16, X split into two     */
+                         /* bf16 terms, products accumulated in fp32 on the matrix cores   */
+} rfsf_ts_shape;
+
+/* Human-readable text for a return code. Never NULL. Host pointer, static storage. */
+const char *rfsf_ts_strerror(int code);
+
+/*
+ * Scratch memory for rfsf_ts_features.
+ *   *recommended_bytes : size at which the whole batch (or a large chunk of it) is
+ *                        processed per kernel launch;
+ *   *minimum_bytes     : smallest size accepted (one chunk of sequences).
+ * Either output pointer may be NULL. The workspace holds the time increments of
+ * the random Fourier features of one chunk of sequences (Sec. 3.2, eq. (rfsf),
+ * the factors nabla phi_m) between the two kernels; its layout is private.
+ */
+int rfsf_ts_workspace_bytes(const rfsf_ts_shape *shape,
+                            size_t *recommended_bytes, size_t *minimum_bytes);
+
+/*
+ * RFSF-TS feature map (Sec. 3.5, eqs. (cs), (ts_def), (ts), (ts_rec) with p = 1, on
+ * top of the random Fourier features of Sec. 3.1, eq. (rff), one independent map
+ * per level as in Sec. 3.2).
+ *
+ * For each sequence n and level m = 1..M:
+ *   theta      = (X[n,t,:] . W[m,:,a]) / lengthscale                a = 0..F-1
+ *   phi_m(x_t) = F^{-1/2} (cos theta_0..F-1, sin theta_0..F-1)      2F numbers: cos block first
+ *   delta_m[k] = phi_m(x_k) - phi_m(x_{k-1})                        k = 1..T
+ *   c_m[k][j]  = sum_{a: hash[m,a] = j} sign[m,a] * delta_m[k][a]   j = 0..D-1
+ *   Phi_m      = sum_{k_1 < ... < k_m} c_1[k_1] (*) ... (*) c_m[k_m]   (*) circular convolution mod D
+ * and out[n, 0] = 1, out[n, 1 + (m-1) D + j] = Phi_m[j].
+ *
+ *   X     [N, L, d]  float32, row-major, contiguous
+ *   W     [M, d, F]  float32 (standard normal draws; the library divides by lengthscale.
+ *                    A caller holding pre-scaled frequencies passes lengthscale = 1)
+ *   hash  [M, 2F]    int32 in [0, D)      (not checked here: see rfsf_ts_validate_tables;
+ *                    out-of-range values are reduced modulo D, never used as addresses)
+ *   sign  [M, 2F]    float32 in {+1, -1}  (only the sign bit is used)
+ *   out   [N, ld_out] float32; columns 0 .. M*D of every row are written, the rest untouched
+ *   workspace, workspace_bytes: scratch from rfsf_ts_workspace_bytes (>= minimum);
+ *                    contents on entry are irrelevant, contents on exit are unspecified
+ *
+ * N = 0 is a successful no-op. L = 1 writes out[n,0] = 1 and zeros. Calls that share a
+ * workspace must be ordered on one stream.
+ */
+int rfsf_ts_features(const rfsf_ts_shape *shape,
+                     const float *X, const float *W,
+                     const int32_t *hash, const float *sign,
+                     float lengthscale,
+                     float *out,
+                     void *workspace, size_t workspace_bytes,
+                     void *hip_stream);
+
+/*
+ * Opt-in device pass that checks the table contents: every hash[m,a] in [0, D) and every
+ * sign[m,a] equal to +1 or -1. Synchronises `hip_stream` (it has to read the verdict).
+ * Returns RFSF_OK or RFSF_E_BAD_TABLE.
+ */
+int rfsf_ts_validate_tables(const int32_t *hash, const float *sign,
+                            int32_t M, int32_t F, int32_t D, void *hip_stream);
+
+/*
+ * Linear Gram of primal features (Sec. 1, "K_XX = P_X P_X^T"; appendix, the feature
+ * classes' call operator):
+ *   K[i, j] = sum_{c < ncols} PhiX[i, c] * PhiY[j, c]          fp32 in, fp32 accumulate
+ *
+ *   PhiX [Nx, ldx], PhiY [Ny, ldy]  float32 row-major, ldx, ldy >= ncols (PhiY may equal PhiX)
+ *   K    [Nx, ldk]                  float32 row-major, ldk >= Ny; columns 0..Ny-1 written
+ *   ncols = 1 + M*D for features made by rfsf_ts_features (the level-0 column is included)
+ * Leading dimensions that are multiples of 4 floats with 16-byte aligned bases take the
+ * vectorised path; anything else is still correct. Nx = 0 or Ny = 0 is a no-op.
+ */
+int rfsf_ts_gram(const float *PhiX, int64_t Nx, int64_t ldx,
+                 const float *PhiY, int64_t Ny, int64_t ldy,
+                 int64_t ncols,
+                 float *K, int64_t ldk,
+                 void *hip_stream);
+
+/*
+ * Optional per-kernel timing for benchmarks (not part of the method). While enabled, every
+ * kernel the library launches is bracketed by HIP events on the stream it is launched on.
+ * rfsf_ts_profile_read waits for those events, adds up the elapsed device time per kernel
+ * class and the number of launches, and (reset != 0) clears the record. Disabled by default;
+ * enabling costs a few microseconds per launch. Process-wide state, not thread-safe.
+ */
+typedef struct {
+    double  ms_rff_increments;   int64_t launches_rff_increments;    /* steps 1-2 kernel */
+    double  ms_sketch_fft_scan;  int64_t launches_sketch_fft_scan;   /* steps 3-4 kernel */
+    double  ms_gram;             int64_t launches_gram;              /* Gram kernel      */
+} rfsf_ts_profile;
+
+int rfsf_ts_profile_enable(int on);
+int rfsf_ts_profile_read(rfsf_ts_profile *out, int reset);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RFSF_TS_H */

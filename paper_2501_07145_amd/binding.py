@@ -1,0 +1,189 @@
+"""Thin ctypes binding of librfsf_ts (argument marshalling only).
+
+Every step of the hot path runs in the HIP kernels behind the C ABI declared in
+include/rfsf_ts.h. PyTorch is used here for device memory and streams, nothing
+else. There is no CPU fallback: if the library is missing or fails to load, the
+calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "librfsf_ts.so")
+_lib = None
+
+
+class RfsfTsError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"librfsf_ts error {code}: {text}")
+        self.code = code
+
+
+class _Shape(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int64), ("L", ctypes.c_int64),
+                ("d", ctypes.c_int32), ("M", ctypes.c_int32), ("F", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("ld_out", ctypes.c_int64), ("rff_bf16", ctypes.c_int32)]
+
+
+class _Profile(ctypes.Structure):
+    _fields_ = [("ms_rff_increments", ctypes.c_double), ("launches_rff_increments", ctypes.c_int64),
+                ("ms_sketch_fft_scan", ctypes.c_double), ("launches_sketch_fft_scan", ctypes.c_int64),
+                ("ms_gram", ctypes.c_double), ("launches_gram", ctypes.c_int64)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load librfsf_ts.so; build it first only if it has never been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from .build import build_library
+        build_library()
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    lib.rfsf_ts_strerror.restype = ctypes.c_char_p
+    lib.rfsf_ts_strerror.argtypes = [ctypes.c_int]
+    lib.rfsf_ts_workspace_bytes.restype = ctypes.c_int
+    lib.rfsf_ts_workspace_bytes.argtypes = [ctypes.POINTER(_Shape), ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    lib.rfsf_ts_features.restype = ctypes.c_int
+    lib.rfsf_ts_features.argtypes = [ctypes.POINTER(_Shape), vp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+    lib.rfsf_ts_validate_tables.restype = ctypes.c_int
+    lib.rfsf_ts_validate_tables.argtypes = [vp, vp, i32, i32, i32, vp]
+    lib.rfsf_ts_gram.restype = ctypes.c_int
+    lib.rfsf_ts_gram.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, i64, vp]
+    lib.rfsf_ts_profile_enable.restype = ctypes.c_int
+    lib.rfsf_ts_profile_enable.argtypes = [ctypes.c_int]
+    lib.rfsf_ts_profile_read.restype = ctypes.c_int
+    lib.rfsf_ts_profile_read.argtypes = [ctypes.POINTER(_Profile), ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def _check(code: int):
+    if code != 0:
+        raise RfsfTsError(code, load_library().rfsf_ts_strerror(code).decode())
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype: torch.dtype, name: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous {dtype}")
+    return t
+
+
+def _shape_of(X, W, hash_, D, ld_out, rff_bf16) -> _Shape:
+    if X.dim() != 3 or W.dim() != 3 or hash_.dim() != 2:
+        raise ValueError("expected X[N,L,d], W[M,d,F], hash[M,2F]")
+    N, L, d = X.shape
+    M, d2, F = W.shape
+    if d2 != d or tuple(hash_.shape) != (M, 2 * F):
+        raise ValueError("inconsistent shapes")
+    return _Shape(N, L, d, M, F, int(D), int(ld_out), int(bool(rff_bf16)))
+
+
+def rfsf_ts_workspace_bytes(N: int, L: int, d: int, M: int, F: int, D: int, rff_bf16: bool = False):
+    """(recommended_bytes, minimum_bytes) of scratch for rfsf_ts_features."""
+    shp = _Shape(N, L, d, M, F, D, 1 + M * D, int(bool(rff_bf16)))
+    rec, mn = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(load_library().rfsf_ts_workspace_bytes(ctypes.byref(shp), ctypes.byref(rec), ctypes.byref(mn)))
+    return int(rec.value), int(mn.value)
+
+
+def feature_row_stride(M: int, D: int) -> int:
+    """Row stride (floats) the binding gives to feature matrices it allocates: 1 + M*D
+    rounded up to a multiple of 4 so that rows stay 16-byte aligned for the Gram."""
+    return (1 + M * D + 3) // 4 * 4
+
+
+def rfsf_ts_features(X: torch.Tensor, W: torch.Tensor, hash: torch.Tensor, sign: torch.Tensor,
+                     lengthscale: float, D: int, out: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None, rff_bf16: bool = False,
+                     stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """RFSF-TS features of a batch: returns a [N, 1 + M*D] float32 view (row stride
+    feature_row_stride(M, D) when allocated here). `out` may be any 2-D float32 device
+    tensor with unit column stride and at least 1 + M*D columns; `workspace` any
+    contiguous uint8 device tensor of at least the minimum size."""
+    lib = load_library()
+    X = _dev(X, torch.float32, "X")
+    W = _dev(W, torch.float32, "W")
+    hash = _dev(hash, torch.int32, "hash")
+    sign = _dev(sign, torch.float32, "sign")
+    N, M = X.shape[0], W.shape[0]
+    ncols = 1 + M * int(D)
+    if out is None:
+        ld = feature_row_stride(M, int(D))
+        out = torch.empty((N, ld), dtype=torch.float32, device=X.device)[:, :ncols]
+    if out.dim() != 2 or out.dtype != torch.float32 or not out.is_cuda or out.shape[0] != N or \
+            out.shape[1] < ncols or (out.shape[1] > 0 and out.stride(1) != 1):
+        raise ValueError("out must be float32 [N, >= 1+M*D] on the device with unit column stride")
+    ld_out = out.stride(0) if N > 1 else max(out.stride(0), out.shape[1])
+    shp = _shape_of(X, W, hash, D, ld_out, rff_bf16)
+    if workspace is None:
+        rec, _ = rfsf_ts_workspace_bytes(shp.N, shp.L, shp.d, shp.M, shp.F, shp.D, rff_bf16)
+        workspace = torch.empty(rec, dtype=torch.uint8, device=X.device)
+    workspace = _dev(workspace, torch.uint8, "workspace")
+    _check(lib.rfsf_ts_features(ctypes.byref(shp), X.data_ptr(), W.data_ptr(), hash.data_ptr(),
+                                sign.data_ptr(), float(lengthscale), out.data_ptr(),
+                                workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return out[:, :ncols]
+
+
+def rfsf_ts_validate_tables(hash: torch.Tensor, sign: torch.Tensor, D: int,
+                            stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Raises RfsfTsError(RFSF_E_BAD_TABLE) unless hash is in [0, D) and sign in {+1, -1}."""
+    hash = _dev(hash, torch.int32, "hash")
+    sign = _dev(sign, torch.float32, "sign")
+    M, twoF = hash.shape
+    _check(load_library().rfsf_ts_validate_tables(hash.data_ptr(), sign.data_ptr(), M, twoF // 2, int(D),
+                                                  _stream_ptr(stream)))
+
+
+def rfsf_ts_gram(PhiX: torch.Tensor, PhiY: Optional[torch.Tensor] = None,
+                 K: Optional[torch.Tensor] = None,
+                 stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """K = PhiX PhiY^T (PhiY defaults to PhiX). Inputs are 2-D float32 device tensors with unit
+    column stride (row strides are passed as leading dimensions)."""
+    lib = load_library()
+    PhiY = PhiX if PhiY is None else PhiY
+    for name, t in (("PhiX", PhiX), ("PhiY", PhiY)):
+        if t.dim() != 2 or t.dtype != torch.float32 or not t.is_cuda or (t.shape[1] > 0 and t.stride(1) != 1):
+            raise ValueError(f"{name} must be float32 [rows, cols] on the device with unit column stride")
+    if PhiX.shape[1] != PhiY.shape[1]:
+        raise ValueError("PhiX and PhiY need the same number of columns")
+    Nx, Ny, ncols = PhiX.shape[0], PhiY.shape[0], PhiX.shape[1]
+    if K is None:
+        K = torch.empty((Nx, Ny), dtype=torch.float32, device=PhiX.device)
+    if K.dim() != 2 or K.dtype != torch.float32 or tuple(K.shape) != (Nx, Ny) or (Ny > 0 and K.stride(1) != 1):
+        raise ValueError("K must be float32 [Nx, Ny] with unit column stride")
+    ldx = PhiX.stride(0) if Nx > 1 else max(ncols, 1)
+    ldy = PhiY.stride(0) if Ny > 1 else max(ncols, 1)
+    ldk = K.stride(0) if Nx > 1 else max(Ny, 1)
+    _check(lib.rfsf_ts_gram(PhiX.data_ptr(), Nx, ldx, PhiY.data_ptr(), Ny, ldy, ncols,
+                            K.data_ptr(), ldk, _stream_ptr(stream)))
+    return K
+
+
+def rfsf_ts_profile_enable(on: bool) -> None:
+    _check(load_library().rfsf_ts_profile_enable(int(bool(on))))
+
+
+def rfsf_ts_profile_read(reset: bool = True) -> dict:
+    """Per-kernel-class device time (ms) and launch counts recorded since the last reset."""
+    p = _Profile()
+    _check(load_library().rfsf_ts_profile_read(ctypes.byref(p), int(bool(reset))))
+    return {f: getattr(p, f) for f, _ in _Profile._fields_}

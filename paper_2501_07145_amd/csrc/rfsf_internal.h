@@ -1,0 +1,53 @@
+// Internal declarations shared by the translation units of librfsf_ts (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace rfsf {
+
+// Row g = n * L + t of the increment workspace holds, for every level m, the 2F numbers
+// phi_m(x_{t+1}) - phi_m(x_t) of sequence n; rows with t = L-1 exist but are never read.
+// Element (g, m, a) sits at ((g * M + m) * 2F + a).
+struct IncrementLayout {
+    int64_t rows;      // N_chunk * L
+    int32_t M, F;
+    __host__ __device__ int64_t row_floats() const { return (int64_t)M * 2 * F; }
+};
+
+// Steps 1-2: random Fourier features of every time point and their time increments
+// for `n_seq` sequences starting at X (already offset to the chunk).
+hipError_t launch_rff_increments(const float *X, const float *W, float inv_lengthscale,
+                                 int64_t n_seq, int64_t L, int d, int M, int F, bool bf16,
+                                 float *dphi, hipStream_t stream);
+
+// Steps 3-4: CountSketch, FFT-domain level recursion over time, inverse transform; writes
+// columns 0 .. M*D of `n_seq` rows of out (already offset to the chunk).
+// `state` is scratch for the generic kernel: n_seq * M * (D/2+1) complex floats.
+hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
+                                  int64_t n_seq, int64_t L, int M, int F, int D,
+                                  float *out, int64_t ld_out, float *state, hipStream_t stream);
+size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D);
+
+// Level-0 column and zero blocks for sequences without increments (L == 1).
+hipError_t launch_fill_trivial(float *out, int64_t n_seq, int64_t ld_out, int64_t ncols, hipStream_t stream);
+
+hipError_t launch_gram(const float *PhiX, int64_t Nx, int64_t ldx, const float *PhiY, int64_t Ny,
+                       int64_t ldy, int64_t ncols, float *K, int64_t ldk, hipStream_t stream);
+
+hipError_t launch_validate_tables(const int32_t *hash, const float *sign, int64_t count, int D,
+                                  int *flag, hipStream_t stream);
+
+
+// Per-kernel event timing (see rfsf_ts_profile_enable). A Scope records a start event when
+// constructed and a stop event when destroyed, if profiling is on.
+enum KernelClass { kRffIncrements = 0, kSketchFftScan = 1, kGram = 2, kNumKernelClasses = 3 };
+struct ProfileScope {
+    ProfileScope(KernelClass k, hipStream_t stream);
+    ~ProfileScope();
+    int slot;
+    hipStream_t stream;
+};
+
+}  // namespace rfsf

@@ -1,0 +1,224 @@
+// C ABI of librfsf_ts: argument checks, chunking over sequences, kernel launches.
+#include "../../include/rfsf_ts.h"
+#include "rfsf_internal.h"
+
+#include <cmath>
+#include <vector>
+
+namespace rfsf {
+namespace {
+struct TimedLaunch { hipEvent_t start, stop; KernelClass k; };
+bool g_profile_on = false;
+std::vector<TimedLaunch> g_launches;
+}  // namespace
+
+ProfileScope::ProfileScope(KernelClass k, hipStream_t s) : slot(-1), stream(s)
+{
+    if (!g_profile_on) return;
+    TimedLaunch t{nullptr, nullptr, k};
+    if (hipEventCreate(&t.start) != hipSuccess) return;
+    if (hipEventCreate(&t.stop) != hipSuccess) { (void)hipEventDestroy(t.start); return; }
+    (void)hipEventRecord(t.start, stream);
+    g_launches.push_back(t);
+    slot = (int)g_launches.size() - 1;
+}
+ProfileScope::~ProfileScope()
+{
+    if (slot >= 0) (void)hipEventRecord(g_launches[slot].stop, stream);
+}
+}  // namespace rfsf
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr size_t kChunkBytesTarget = (size_t)32 << 30;   // increments held per launch, at most
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+bool is_pow2_in_range(int32_t D) { return D >= 2 && D <= 4096 && (D & (D - 1)) == 0; }
+
+int check_shape(const rfsf_ts_shape *s)
+{
+    if (!s) return RFSF_E_NULLPTR;
+    if (s->N < 0 || s->L < 1 || s->d < 1 || s->M < 1 || s->F < 1) return RFSF_E_BAD_SHAPE;
+    if (s->N > ((int64_t)1 << 40) || s->L > ((int64_t)1 << 40) || s->d > (1 << 20) || s->M > (1 << 10) ||
+        s->F > (1 << 24))
+        return RFSF_E_BAD_SHAPE;
+    if (!is_pow2_in_range(s->D)) return RFSF_E_D_NOT_POW2;
+    if (s->ld_out < 1 + (int64_t)s->M * s->D) return RFSF_E_BAD_STRIDE;
+    return RFSF_OK;
+}
+
+// Bytes of workspace one sequence needs: its increment rows plus its accumulator state.
+void per_sequence_bytes(const rfsf_ts_shape *s, size_t *incr, size_t *state)
+{
+    *incr = (size_t)s->L * (size_t)s->M * 2u * (size_t)s->F * sizeof(float);
+    *state = rfsf::sketch_fft_scan_state_bytes(1, s->M, s->D);
+}
+
+int64_t chunk_for(const rfsf_ts_shape *s, size_t bytes)
+{
+    size_t incr, state;
+    per_sequence_bytes(s, &incr, &state);
+    if (bytes < 2 * kAlign) return 0;
+    const size_t usable = bytes - 2 * kAlign;            // room for aligning the two sections
+    return (int64_t)(usable / (incr + state));
+}
+
+}  // namespace
+
+extern "C" const char *rfsf_ts_strerror(int code)
+{
+    switch (code) {
+        case RFSF_OK: return "success";
+        case RFSF_E_NULLPTR: return "a required pointer is NULL";
+        case RFSF_E_BAD_SHAPE: return "bad shape: need N >= 0, L >= 1, d >= 1, M >= 1, F >= 1 within limits";
+        case RFSF_E_D_NOT_POW2: return "D must be a power of two in [2, 4096]";
+        case RFSF_E_BAD_STRIDE: return "leading dimension smaller than the row length";
+        case RFSF_E_BAD_LENGTHSCALE: return "lengthscale must be finite and > 0";
+        case RFSF_E_WORKSPACE_TOO_SMALL: return "workspace smaller than rfsf_ts_workspace_bytes' minimum";
+        case RFSF_E_HIP: return "HIP runtime error";
+        case RFSF_E_BAD_TABLE: return "hash outside [0, D) or sign not +-1";
+        case RFSF_E_UNSUPPORTED: return "configuration not supported by this build";
+        default: return "unknown rfsf_ts error code";
+    }
+}
+
+extern "C" int rfsf_ts_workspace_bytes(const rfsf_ts_shape *shape, size_t *recommended_bytes,
+                                       size_t *minimum_bytes)
+{
+    const int rc = check_shape(shape);
+    if (rc != RFSF_OK) return rc;
+    size_t incr, state;
+    per_sequence_bytes(shape, &incr, &state);
+    const size_t per = incr + state;
+    int64_t chunk = (int64_t)(kChunkBytesTarget / per);
+    if (chunk < 1) chunk = 1;
+    if (chunk > shape->N) chunk = shape->N > 0 ? shape->N : 1;
+    // equal-sized chunks: no small trailing launch
+    if (shape->N > 0) {
+        const int64_t nchunks = (shape->N + chunk - 1) / chunk;
+        chunk = (shape->N + nchunks - 1) / nchunks;
+    }
+    if (recommended_bytes) *recommended_bytes = (size_t)chunk * per + 2 * kAlign;
+    if (minimum_bytes) *minimum_bytes = per + 2 * kAlign;
+    return RFSF_OK;
+}
+
+extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, const float *W,
+                                const int32_t *hash, const float *sign, float lengthscale, float *out,
+                                void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_shape(shape);
+    if (rc != RFSF_OK) return rc;
+    if (!(lengthscale > 0.0f) || !std::isfinite(lengthscale)) return RFSF_E_BAD_LENGTHSCALE;
+    if (shape->N == 0) return RFSF_OK;
+    if (!X || !W || !hash || !sign || !out) return RFSF_E_NULLPTR;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t ncols = 1 + (int64_t)shape->M * shape->D;
+
+    if (shape->L == 1) {      // no increments: empty sums
+        return rfsf::launch_fill_trivial(out, shape->N, shape->ld_out, ncols, stream) == hipSuccess
+                   ? RFSF_OK : RFSF_E_HIP;
+    }
+    if ((int64_t)shape->M * ((shape->F + 255) / 256) > 65535) return RFSF_E_UNSUPPORTED;
+    if (!workspace) return RFSF_E_NULLPTR;
+    int64_t chunk = chunk_for(shape, workspace_bytes);
+    if (chunk < 1) return RFSF_E_WORKSPACE_TOO_SMALL;
+    if (chunk > shape->N) chunk = shape->N;
+
+    size_t incr, state_b;
+    per_sequence_bytes(shape, &incr, &state_b);
+    char *base = static_cast<char *>(workspace);
+    const size_t mis = (size_t)(reinterpret_cast<uintptr_t>(base) % kAlign);
+    char *p_incr = base + (mis ? kAlign - mis : 0);
+    char *p_state = p_incr + align_up((size_t)chunk * incr);
+    float *dphi = reinterpret_cast<float *>(p_incr);
+    float *state = reinterpret_cast<float *>(p_state);
+
+    const float inv_ls = 1.0f / lengthscale;
+    for (int64_t n0 = 0; n0 < shape->N; n0 += chunk) {
+        const int64_t cnt = shape->N - n0 < chunk ? shape->N - n0 : chunk;
+        {
+            rfsf::ProfileScope scope(rfsf::kRffIncrements, stream);
+            if (rfsf::launch_rff_increments(X + n0 * shape->L * shape->d, W, inv_ls, cnt, shape->L, shape->d,
+                                            shape->M, shape->F, shape->rff_bf16 != 0, dphi, stream) != hipSuccess)
+                return RFSF_E_HIP;
+        }
+        {
+            rfsf::ProfileScope scope(rfsf::kSketchFftScan, stream);
+            if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, cnt, shape->L, shape->M, shape->F, shape->D,
+                                             out + n0 * shape->ld_out, shape->ld_out, state, stream) != hipSuccess)
+                return RFSF_E_HIP;
+        }
+    }
+    return RFSF_OK;
+}
+
+extern "C" int rfsf_ts_validate_tables(const int32_t *hash, const float *sign, int32_t M, int32_t F,
+                                       int32_t D, void *hip_stream)
+{
+    if (!hash || !sign) return RFSF_E_NULLPTR;
+    if (M < 1 || F < 1) return RFSF_E_BAD_SHAPE;
+    if (!is_pow2_in_range(D)) return RFSF_E_D_NOT_POW2;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int *flag = nullptr;
+    if (hipMalloc(&flag, sizeof(int)) != hipSuccess) return RFSF_E_HIP;
+    int host = 0;
+    int rc = RFSF_OK;
+    if (hipMemcpyAsync(flag, &host, sizeof(int), hipMemcpyHostToDevice, stream) != hipSuccess ||
+        rfsf::launch_validate_tables(hash, sign, (int64_t)M * 2 * F, D, flag, stream) != hipSuccess ||
+        hipMemcpyAsync(&host, flag, sizeof(int), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess)
+        rc = RFSF_E_HIP;
+    (void)hipFree(flag);
+    if (rc != RFSF_OK) return rc;
+    return host ? RFSF_E_BAD_TABLE : RFSF_OK;
+}
+
+extern "C" int rfsf_ts_gram(const float *PhiX, int64_t Nx, int64_t ldx, const float *PhiY, int64_t Ny,
+                            int64_t ldy, int64_t ncols, float *K, int64_t ldk, void *hip_stream)
+{
+    if (Nx < 0 || Ny < 0 || ncols < 0) return RFSF_E_BAD_SHAPE;
+    if (ldx < ncols || ldy < ncols || ldk < Ny) return RFSF_E_BAD_STRIDE;
+    if (Nx == 0 || Ny == 0) return RFSF_OK;
+    if (!PhiX || !PhiY || !K) return RFSF_E_NULLPTR;
+    if ((Nx + 63) / 64 > 65535 || (Ny + 63) / 64 > 2147483647) return RFSF_E_UNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    rfsf::ProfileScope scope(rfsf::kGram, stream);
+    return rfsf::launch_gram(PhiX, Nx, ldx, PhiY, Ny, ldy, ncols, K, ldk, stream) == hipSuccess
+               ? RFSF_OK : RFSF_E_HIP;
+}
+
+extern "C" int rfsf_ts_profile_enable(int on)
+{
+    rfsf::g_profile_on = on != 0;
+    return RFSF_OK;
+}
+
+extern "C" int rfsf_ts_profile_read(rfsf_ts_profile *out, int reset)
+{
+    if (!out) return RFSF_E_NULLPTR;
+    *out = rfsf_ts_profile{0.0, 0, 0.0, 0, 0.0, 0};
+    int rc = RFSF_OK;
+    for (const rfsf::TimedLaunch &t : rfsf::g_launches) {
+        float ms = 0.f;
+        if (hipEventSynchronize(t.stop) != hipSuccess || hipEventElapsedTime(&ms, t.start, t.stop) != hipSuccess) {
+            rc = RFSF_E_HIP;
+            continue;
+        }
+        switch (t.k) {
+            case rfsf::kRffIncrements: out->ms_rff_increments += ms; ++out->launches_rff_increments; break;
+            case rfsf::kSketchFftScan: out->ms_sketch_fft_scan += ms; ++out->launches_sketch_fft_scan; break;
+            default: out->ms_gram += ms; ++out->launches_gram; break;
+        }
+    }
+    if (reset) {
+        for (const rfsf::TimedLaunch &t : rfsf::g_launches) {
+            (void)hipEventDestroy(t.start);
+            (void)hipEventDestroy(t.stop);
+        }
+        rfsf::g_launches.clear();
+    }
+    return rc;
+}

@@ -1,0 +1,183 @@
+// Steps 3-4 of the RFSF-TS path: CountSketch of every feature increment (Sec. 3.5, eq. (cs)),
+// the level recursion over time in the Fourier domain (eq. (ts_rec), second line, p = 1) and
+// one inverse transform per level at the end.
+//
+// With C_m[k] = FFT(CS_m(delta_m[k])) and per-bin accumulators A_m (A_0 = 1), one time step is
+//     A_m <- A_m + A_{m-1}(before this step) * C_m[k],   m = 1..M,
+// which is the exclusive prefix sum over time of level m-1 times the sketched increment of
+// level m, summed over time; Phi_m = IFFT(A_m). Two consecutive time steps share one complex
+// FFT (real parts = step k, imaginary parts = step k+1) and are separated again per bin.
+#include "rfsf_internal.h"
+
+namespace rfsf {
+namespace {
+
+__device__ __forceinline__ float2 cmul(float2 a, float2 b)
+{
+    return make_float2(fmaf(a.x, b.x, -a.y * b.y), fmaf(a.x, b.y, a.y * b.x));
+}
+__device__ __forceinline__ float2 cfma(float2 a, float2 b, float2 c)   // a * b + c
+{
+    return make_float2(fmaf(a.x, b.x, fmaf(-a.y, b.y, c.x)), fmaf(a.x, b.y, fmaf(a.y, b.x, c.y)));
+}
+
+// Forward DFT of length D = 2^log2D by radix-2 Stockham passes through two LDS buffers, all
+// threads of the workgroup cooperating. tw[t] = exp(-2 pi i t / D), t < D/2. Returns the
+// buffer that holds the result in natural order.
+__device__ float2 *fft_workgroup(float2 *in, float2 *out, const float2 *tw, int D, int log2D)
+{
+    for (int s = 0; s < log2D; ++s) {
+        const int Ns = 1 << s;
+        for (int j = threadIdx.x; j < D / 2; j += blockDim.x) {
+            const int k = j & (Ns - 1);
+            const float2 w = tw[k << (log2D - 1 - s)];
+            const float2 a = in[j];
+            const float2 b = cmul(in[j + D / 2], w);
+            const int j0 = ((j - k) << 1) + k;
+            out[j0] = make_float2(a.x + b.x, a.y + b.y);
+            out[j0 + Ns] = make_float2(a.x - b.x, a.y - b.y);
+        }
+        __syncthreads();
+        float2 *t = in; in = out; out = t;
+    }
+    return in;
+}
+
+// Generic kernel: any power-of-two D in [2, 4096], any M and F. One workgroup per sequence,
+// accumulators in global scratch. Correct everywhere, tuned nowhere.
+__global__ __launch_bounds__(256) void sketch_fft_scan_generic(
+    const float *__restrict__ dphi, const int32_t *__restrict__ hash, const float *__restrict__ sign,
+    int64_t L, int M, int F, int D, int log2D, float *__restrict__ out, int64_t ld_out,
+    float2 *__restrict__ state)
+{
+    extern __shared__ float2 sm[];
+    const int nb = D / 2 + 1;
+    float2 *buf0 = sm, *buf1 = sm + D, *tw = sm + 2 * D;
+    float2 *P0 = tw + D / 2, *P1 = P0 + nb;
+    const int64_t n = blockIdx.x;
+    const int64_t T = L - 1;
+    const int twoF = 2 * F;
+    const int64_t rf = (int64_t)M * twoF;
+    float2 *A = state + n * M * nb;
+
+    for (int k = threadIdx.x; k < D / 2; k += blockDim.x) {
+        float s, c;
+        sincospif(2.0f * (float)k / (float)D, &s, &c);
+        tw[k] = make_float2(c, -s);
+    }
+    for (int i = threadIdx.x; i < M * nb; i += blockDim.x) A[i] = make_float2(0.f, 0.f);
+    __syncthreads();
+
+    for (int64_t k = 0; k < T; k += 2) {
+        const bool two = k + 1 < T;
+        const float *row0 = dphi + (n * L + k) * rf;
+        const float *row1 = row0 + rf;
+        for (int m = 0; m < M; ++m) {
+            for (int i = threadIdx.x; i < D; i += blockDim.x) buf0[i] = make_float2(0.f, 0.f);
+            __syncthreads();
+            for (int a = threadIdx.x; a < twoF; a += blockDim.x) {
+                const int h = hash[m * twoF + a] & (D - 1);
+                const float s = copysignf(0.5f, sign[m * twoF + a]);
+                const float v0 = row0[m * twoF + a];
+                const float v1 = two ? row1[m * twoF + a] : 0.f;
+                atomicAdd(&buf0[h].x, s * v0);
+                atomicAdd(&buf0[h].y, s * v1);
+            }
+            __syncthreads();
+            const float2 *Z = fft_workgroup(buf0, buf1, tw, D, log2D);
+            for (int f = threadIdx.x; f < nb; f += blockDim.x) {
+                const float2 z = Z[f], zc = Z[(D - f) & (D - 1)];
+                const float2 C0 = make_float2(z.x + zc.x, z.y - zc.y);
+                const float2 C1 = make_float2(z.y + zc.y, zc.x - z.x);
+                const float2 p0 = m == 0 ? make_float2(1.f, 0.f) : P0[f];
+                const float2 p1 = m == 0 ? make_float2(1.f, 0.f) : P1[f];
+                const float2 a_old = A[m * nb + f];
+                const float2 a_mid = cfma(p0, C0, a_old);
+                const float2 a_new = cfma(p1, C1, a_mid);
+                A[m * nb + f] = a_new;
+                P0[f] = a_old;
+                P1[f] = a_mid;
+            }
+            __syncthreads();
+        }
+    }
+
+    // Phi_m = IFFT(A_m) = Re(FFT(conj(Y))) / D with Y the Hermitian extension of A_m.
+    const float invD = 1.0f / (float)D;
+    float *row = out + n * ld_out;
+    if (threadIdx.x == 0) row[0] = 1.0f;
+    for (int m = 0; m < M; ++m) {
+        for (int f = threadIdx.x; f < nb; f += blockDim.x) {
+            const float2 y = A[m * nb + f];
+            buf0[f] = make_float2(y.x, -y.y);
+            if (f > 0 && f < D / 2) buf0[D - f] = y;
+        }
+        __syncthreads();
+        const float2 *Z = fft_workgroup(buf0, buf1, tw, D, log2D);
+        for (int j = threadIdx.x; j < D; j += blockDim.x) row[1 + (int64_t)m * D + j] = Z[j].x * invD;
+        __syncthreads();
+    }
+}
+
+__global__ void fill_trivial_kernel(float *out, int64_t n_seq, int64_t ld_out, int64_t ncols)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_seq * ncols) return;
+    const int64_t n = i / ncols, c = i % ncols;
+    out[n * ld_out + c] = c == 0 ? 1.0f : 0.0f;
+}
+
+__global__ void validate_tables_kernel(const int32_t *hash, const float *sign, int64_t count, int D, int *flag)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    const bool ok = hash[i] >= 0 && hash[i] < D && (sign[i] == 1.0f || sign[i] == -1.0f);
+    if (!ok) atomicOr(flag, 1);
+}
+
+}  // namespace
+
+size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D)
+{
+    return (size_t)n_seq * (size_t)M * (size_t)(D / 2 + 1) * sizeof(float2);
+}
+
+hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
+                                  int64_t n_seq, int64_t L, int M, int F, int D,
+                                  float *out, int64_t ld_out, float *state, hipStream_t stream)
+{
+    if (n_seq == 0) return hipSuccess;
+    int log2D = 0;
+    while ((1 << log2D) < D) ++log2D;
+    const size_t lds = sizeof(float2) * (size_t)(2 * D + D / 2 + 2 * (D / 2 + 1));
+    static size_t lds_granted = 0;        // per process; raising the limit is idempotent
+    if (lds > 64 * 1024 && lds > lds_granted) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(sketch_fft_scan_generic),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        lds_granted = lds;
+    }
+    hipLaunchKernelGGL(sketch_fft_scan_generic, dim3((unsigned)n_seq), dim3(256), lds, stream,
+                       dphi, hash, sign, L, M, F, D, log2D, out, ld_out, reinterpret_cast<float2 *>(state));
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_trivial(float *out, int64_t n_seq, int64_t ld_out, int64_t ncols, hipStream_t stream)
+{
+    const int64_t total = n_seq * ncols;
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_trivial_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       out, n_seq, ld_out, ncols);
+    return hipGetLastError();
+}
+
+hipError_t launch_validate_tables(const int32_t *hash, const float *sign, int64_t count, int D,
+                                  int *flag, hipStream_t stream)
+{
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(validate_tables_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream,
+                       hash, sign, count, D, flag);
+    return hipGetLastError();
+}
+
+}  // namespace rfsf

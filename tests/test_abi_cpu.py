@@ -1,0 +1,103 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol
+the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2501_07145_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b(rfsf_ts_[a-z_0-9]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = binding.load_library()
+    names = _declared_functions()
+    assert {"rfsf_ts_features", "rfsf_ts_gram", "rfsf_ts_workspace_bytes", "rfsf_ts_strerror",
+            "rfsf_ts_validate_tables"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_strerror_covers_all_codes():
+    lib = binding.load_library()
+    seen = set()
+    for code in range(0, -10, -1):
+        s = lib.rfsf_ts_strerror(code).decode()
+        assert s and "unknown" not in s
+        seen.add(s)
+    assert len(seen) == 10
+    assert "unknown" in lib.rfsf_ts_strerror(-99).decode()
+
+
+def _shape(**kw):
+    base = dict(N=4, L=8, d=3, M=2, F=4, D=8, ld_out=17, rff_bf16=0)
+    base.update(kw)
+    return binding._Shape(**base)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(N=-1), -2), (dict(L=0), -2), (dict(d=0), -2), (dict(M=0), -2), (dict(F=0), -2),
+    (dict(D=6), -3), (dict(D=1), -3), (dict(D=8192), -3), (dict(D=0), -3), (dict(ld_out=16), -4),
+])
+def test_shape_validation(kw, code):
+    lib = binding.load_library()
+    rec, mn = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    shp = _shape(**kw)
+    assert lib.rfsf_ts_workspace_bytes(ctypes.byref(shp), ctypes.byref(rec), ctypes.byref(mn)) == code
+    # the feature call checks the shape before anything else (fake non-null pointers are never read)
+    assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, 1.0, 256, 256, 1 << 20, None) == code
+
+
+def test_argument_validation_without_device_access():
+    lib = binding.load_library()
+    shp = _shape()
+    assert lib.rfsf_ts_features(None, 256, 256, 256, 256, 1.0, 256, 256, 1 << 20, None) == -1
+    assert lib.rfsf_ts_features(ctypes.byref(shp), None, 256, 256, 256, 1.0, 256, 256, 1 << 20, None) == -1
+    assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, 1.0, 256, None, 1 << 20, None) == -1
+    for bad in (0.0, -1.0, float("inf"), float("nan")):
+        assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, bad, 256, 256, 1 << 20, None) == -5
+    assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, 1.0, 256, 256, 16, None) == -6
+    empty = _shape(N=0)
+    assert lib.rfsf_ts_features(ctypes.byref(empty), None, None, None, None, 1.0, None, None, 0, None) == 0
+    # Gram
+    assert lib.rfsf_ts_gram(256, 4, 8, 256, 4, 8, 9, 256, 4, None) == -4
+    assert lib.rfsf_ts_gram(256, 4, 9, 256, 4, 9, 9, 256, 3, None) == -4
+    assert lib.rfsf_ts_gram(256, -1, 9, 256, 4, 9, 9, 256, 4, None) == -2
+    assert lib.rfsf_ts_gram(None, 4, 9, 256, 4, 9, 9, 256, 4, None) == -1
+    assert lib.rfsf_ts_gram(None, 0, 9, None, 4, 9, 9, None, 4, None) == 0
+    assert lib.rfsf_ts_validate_tables(None, 256, 2, 4, 8, None) == -1
+    assert lib.rfsf_ts_validate_tables(256, 256, 2, 4, 12, None) == -3
+
+
+def test_workspace_sizes():
+    rec, mn = binding.rfsf_ts_workspace_bytes(1000, 100, 8, 4, 128, 256)
+    per_seq = 100 * 4 * 256 * 4 + 4 * 129 * 8
+    assert mn == per_seq + 512 and rec == 1000 * per_seq + 512
+    rec_big, mn_big = binding.rfsf_ts_workspace_bytes(50000, 64, 64, 5, 1024, 2048)
+    assert mn_big <= rec_big <= (33 << 30)
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    X = torch.zeros(2, 4, 3)
+    W = torch.zeros(2, 3, 4)
+    h = torch.zeros(2, 8, dtype=torch.int32)
+    s = torch.ones(2, 8)
+    with pytest.raises(ValueError):
+        binding.rfsf_ts_features(X, W, h, s, 1.0, 8)
+    with pytest.raises(ValueError):
+        binding.rfsf_ts_gram(torch.zeros(3, 5))

@@ -1,0 +1,172 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
+seeded inputs, element by element, block-normalised (max relative error per feature block)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2501_07145_amd as rfsf
+from paper_2501_07145_amd import binding, workloads as wl
+from tests.parity import BF16_BLOCK_TOL, FP32_BLOCK_TOL, GRAM_TOL, block_errors, gram_error
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(inp):
+    return {k: (torch.from_numpy(v).cuda() if isinstance(v, np.ndarray) else v) for k, v in inp.items()}
+
+
+def _gpu_features(inp, D, **kw):
+    t = _dev(inp)
+    out = rfsf.rfsf_ts_features(t["X"], t["W"], t["hash"], t["sign"], inp["lengthscale"], D, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+def _random_case(seed, N, L, d, M, F, D, ls=1.5, step=0.3):
+    rng = np.random.default_rng(seed)
+    X = np.cumsum(rng.standard_normal((N, L, d)) * step, axis=1).astype(np.float32)
+    W = rng.standard_normal((M, d, F)).astype(np.float32)
+    hash_ = rng.integers(0, D, size=(M, 2 * F)).astype(np.int32)
+    sign = (2.0 * rng.integers(0, 2, size=(M, 2 * F)) - 1.0).astype(np.float32)
+    return {"X": X, "W": W, "hash": hash_, "sign": sign, "lengthscale": float(np.float32(ls))}
+
+
+def _check(inp, D, oracle, tol=FP32_BLOCK_TOL, **kw):
+    M = inp["W"].shape[0]
+    got = _gpu_features(inp, D, **kw).cpu().numpy()
+    want = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D)
+    err = block_errors(got, want, M, D)
+    assert np.all(err <= tol), f"block errors {err} exceed {tol}"
+    return got, want, err
+
+
+def test_tiny_all_rows(oracle):
+    w = wl.WORKLOADS["tiny"]
+    inp = wl.make_inputs(w, 0)
+    got, want, err = _check(inp, w.D, oracle)
+    print("tiny block errors", err)
+    K = rfsf.rfsf_ts_gram(torch.from_numpy(got).cuda())
+    torch.cuda.synchronize()
+    assert gram_error(K.cpu().numpy(), oracle.gram(want)) <= GRAM_TOL
+
+
+def test_small_64_rows(oracle):
+    w = wl.WORKLOADS["small"].scaled(N=64)
+    inp = wl.make_inputs(w, 0)
+    _, _, err = _check(inp, w.D, oracle)
+    print("small[64] block errors", err)
+
+
+@pytest.mark.parametrize("N,L,d,M,F,D", [
+    (5, 37, 5, 3, 24, 32),      # F not a multiple of the tile, D != 2F, odd number of increments
+    (3, 36, 1, 2, 1, 2),        # smallest d, F, D
+    (4, 9, 7, 1, 40, 128),      # one level
+    (2, 2, 3, 4, 16, 16),       # one increment: levels above 1 vanish
+    (2, 3, 3, 4, 16, 16),       # two increments: levels above 2 vanish
+    (7, 65, 19, 6, 70, 64),     # several row tiles with a ragged tail, six levels, D < 2F
+    (2, 20, 4, 2, 8, 4096),     # largest D
+    (3, 300, 33, 3, 130, 512),  # d above one MFMA K-slab, F with a ragged column tile
+    (1, 1000, 2, 5, 16, 8),     # long and narrow
+])
+def test_ragged_shapes(oracle, N, L, d, M, F, D):
+    inp = _random_case(100 + N + L + D, N, L, d, M, F, D)
+    _, _, err = _check(inp, D, oracle)
+    print(f"N={N} L={L} d={d} M={M} F={F} D={D} block errors", err)
+
+
+def test_no_increments_and_empty_batch(oracle):
+    inp = _random_case(1, 3, 1, 2, 3, 4, 8)
+    got = _gpu_features(inp, 8).cpu().numpy()
+    assert np.all(got[:, 0] == 1.0) and np.all(got[:, 1:] == 0.0)
+    empty = _random_case(2, 0, 5, 2, 3, 4, 8)
+    assert tuple(_gpu_features(empty, 8).shape) == (0, 25)
+
+
+def test_chunked_execution_matches(oracle):
+    """A workspace that holds only a few sequences forces several launches per call."""
+    inp = _random_case(3, 11, 21, 4, 3, 16, 32)
+    _, mn = rfsf.rfsf_ts_workspace_bytes(11, 21, 4, 3, 16, 32)
+    for nseq in (1, 3):
+        ws = torch.empty(512 + nseq * (mn - 512), dtype=torch.uint8, device="cuda")
+        _check(inp, 32, oracle, workspace=ws)
+    with pytest.raises(binding.RfsfTsError) as e:
+        _gpu_features(inp, 32, workspace=torch.empty(mn - 1, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == -6
+
+
+def test_row_stride_and_untouched_padding(oracle):
+    inp = _random_case(4, 6, 15, 3, 2, 8, 16)
+    ncols = 1 + 2 * 16
+    buf = torch.full((6, ncols + 7), -7.0, dtype=torch.float32, device="cuda")
+    _check(inp, 16, oracle, out=buf)
+    assert torch.all(buf[:, ncols:] == -7.0)
+
+
+def test_hash_is_reduced_modulo_D_and_sign_uses_only_the_sign_bit(oracle):
+    inp = _random_case(5, 4, 12, 3, 2, 8, 16)
+    wild = dict(inp)
+    wild["hash"] = (inp["hash"] + 16 * np.arange(16, dtype=np.int32)[None, :]).astype(np.int32)
+    wild["sign"] = (inp["sign"] * 3.5).astype(np.float32)
+    got = _gpu_features(wild, 16).cpu().numpy()
+    want = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], 16)
+    assert np.all(block_errors(got, want, 2, 16) <= FP32_BLOCK_TOL)
+
+
+def test_validate_tables():
+    inp = _dev(_random_case(6, 1, 4, 2, 2, 8, 16))
+    rfsf.rfsf_ts_validate_tables(inp["hash"], inp["sign"], 16)
+    bad_h = inp["hash"].clone()
+    bad_h[1, 3] = 16
+    with pytest.raises(binding.RfsfTsError) as e:
+        rfsf.rfsf_ts_validate_tables(bad_h, inp["sign"], 16)
+    assert e.value.code == -8
+    bad_s = inp["sign"].clone()
+    bad_s[0, 0] = 0.5
+    with pytest.raises(binding.RfsfTsError):
+        rfsf.rfsf_ts_validate_tables(inp["hash"], bad_s, 16)
+
+
+def test_large_angles(oracle):
+    """Angles of a few hundred radians: the range reduction must stay accurate."""
+    inp = _random_case(7, 4, 30, 3, 3, 32, 64, ls=0.02, step=0.05)
+    _check(inp, 64, oracle)
+
+
+def test_runs_on_a_side_stream(oracle):
+    inp = _random_case(8, 5, 18, 3, 3, 16, 32)
+    s = torch.cuda.Stream()
+    t = _dev(inp)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        out = rfsf.rfsf_ts_features(t["X"], t["W"], t["hash"], t["sign"], inp["lengthscale"], 32, stream=s)
+        K = rfsf.rfsf_ts_gram(out, stream=s)
+    s.synchronize()
+    want = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], 32)
+    assert np.all(block_errors(out.cpu().numpy(), want, 3, 32) <= FP32_BLOCK_TOL)
+    assert gram_error(K.cpu().numpy(), oracle.gram(want)) <= GRAM_TOL
+
+
+# ------------------------------------------------------------------ Gram
+@pytest.mark.parametrize("Nx,Ny,C,pad", [(16, 16, 193, 0), (70, 45, 1025, 3), (1, 1, 1, 0), (129, 257, 37, 1),
+                                         (300, 64, 2049, 0), (65, 130, 516, 0)])
+def test_gram_against_oracle(oracle, Nx, Ny, C, pad):
+    rng = np.random.default_rng(Nx + Ny + C)
+    A = rng.standard_normal((Nx, C + pad)).astype(np.float32)
+    B = rng.standard_normal((Ny, C + pad)).astype(np.float32)
+    K = rfsf.rfsf_ts_gram(torch.from_numpy(A).cuda()[:, :C], torch.from_numpy(B).cuda()[:, :C])
+    torch.cuda.synchronize()
+    assert gram_error(K.cpu().numpy(), oracle.gram(A[:, :C], B[:, :C])) <= GRAM_TOL
+
+
+def test_gram_unaligned_base_and_strided_output(oracle):
+    rng = np.random.default_rng(9)
+    A = rng.standard_normal((33, 101)).astype(np.float32)
+    flat = torch.zeros(33 * 101 + 1, dtype=torch.float32, device="cuda")
+    flat[1:] = torch.from_numpy(A).cuda().reshape(-1)
+    Ad = flat[1:].view(33, 101)                      # base is 4 bytes off a 16-byte boundary
+    Kbuf = torch.full((33, 40), -3.0, dtype=torch.float32, device="cuda")
+    rfsf.rfsf_ts_gram(Ad, Ad, K=Kbuf[:, :33])
+    torch.cuda.synchronize()
+    assert gram_error(Kbuf[:, :33].cpu().numpy(), oracle.gram(A)) <= GRAM_TOL
+    assert torch.all(Kbuf[:, 33:] == -3.0)
+    assert torch.equal(Kbuf[:, :33], Kbuf[:, :33].T.contiguous())
