@@ -84,7 +84,7 @@ hipError_t launch_rff_increments(const float *X, const float *W, float inv_lengt
     const int64_t nblk = (rows - 1 + rows_per_block - 1) / rows_per_block;
     const int fblocks = (F + 255) / 256;
     dim3 grid((unsigned)nblk, (unsigned)(M * fblocks));
-    const float scale = 1.0f / sqrtf((float)F);
+    const float scale = 0.5f / sqrtf((float)F);    // the consumer's two-for-one FFT wants halved increments
     hipLaunchKernelGGL(rff_increments_valu, grid, dim3(256), sizeof(float) * kRowsPerTile * d, stream,
                        X, W, inv_lengthscale, scale, rows, d, M, F, rows_per_block, dphi);
     return hipGetLastError();

@@ -56,13 +56,19 @@ void per_sequence_bytes(const rfsf_ts_shape *s, size_t *incr, size_t *state)
     *state = rfsf::sketch_fft_scan_state_bytes(1, s->M, s->D);
 }
 
+// Fixed part: packed hash/sign table plus room for aligning the three sections.
+size_t fixed_bytes(const rfsf_ts_shape *s)
+{
+    return align_up((size_t)s->M * 2u * (size_t)s->F * sizeof(uint32_t)) + 3 * kAlign;
+}
+
 int64_t chunk_for(const rfsf_ts_shape *s, size_t bytes)
 {
     size_t incr, state;
     per_sequence_bytes(s, &incr, &state);
-    if (bytes < 2 * kAlign) return 0;
-    const size_t usable = bytes - 2 * kAlign;            // room for aligning the two sections
-    return (int64_t)(usable / (incr + state));
+    const size_t fixed = fixed_bytes(s);
+    if (bytes < fixed) return 0;
+    return (int64_t)((bytes - fixed) / (incr + state));
 }
 
 }  // namespace
@@ -100,8 +106,8 @@ extern "C" int rfsf_ts_workspace_bytes(const rfsf_ts_shape *shape, size_t *recom
         const int64_t nchunks = (shape->N + chunk - 1) / chunk;
         chunk = (shape->N + nchunks - 1) / nchunks;
     }
-    if (recommended_bytes) *recommended_bytes = (size_t)chunk * per + 2 * kAlign;
-    if (minimum_bytes) *minimum_bytes = per + 2 * kAlign;
+    if (recommended_bytes) *recommended_bytes = (size_t)chunk * per + fixed_bytes(shape);
+    if (minimum_bytes) *minimum_bytes = per + fixed_bytes(shape);
     return RFSF_OK;
 }
 
@@ -131,10 +137,14 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
     per_sequence_bytes(shape, &incr, &state_b);
     char *base = static_cast<char *>(workspace);
     const size_t mis = (size_t)(reinterpret_cast<uintptr_t>(base) % kAlign);
-    char *p_incr = base + (mis ? kAlign - mis : 0);
+    char *p_table = base + (mis ? kAlign - mis : 0);
+    char *p_incr = p_table + align_up((size_t)shape->M * 2u * (size_t)shape->F * sizeof(uint32_t));
     char *p_state = p_incr + align_up((size_t)chunk * incr);
     float *dphi = reinterpret_cast<float *>(p_incr);
     float *state = reinterpret_cast<float *>(p_state);
+    uint32_t *table = reinterpret_cast<uint32_t *>(p_table);
+    if (rfsf::launch_pack_tables(hash, sign, shape->M, shape->F, shape->D, table, stream) != hipSuccess)
+        return RFSF_E_HIP;
 
     const float inv_ls = 1.0f / lengthscale;
     for (int64_t n0 = 0; n0 < shape->N; n0 += chunk) {
@@ -147,7 +157,7 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
         }
         {
             rfsf::ProfileScope scope(rfsf::kSketchFftScan, stream);
-            if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, cnt, shape->L, shape->M, shape->F, shape->D,
+            if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, table, cnt, shape->L, shape->M, shape->F, shape->D,
                                              out + n0 * shape->ld_out, shape->ld_out, state, stream) != hipSuccess)
                 return RFSF_E_HIP;
         }

@@ -8,6 +8,7 @@
 // level m, summed over time; Phi_m = IFFT(A_m). Two consecutive time steps share one complex
 // FFT (real parts = step k, imaginary parts = step k+1) and are separated again per bin.
 #include "rfsf_internal.h"
+#include "sketch_fft_scan_tuned.h"
 
 namespace rfsf {
 namespace {
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
             __syncthreads();
             for (int a = threadIdx.x; a < twoF; a += blockDim.x) {
                 const int h = hash[m * twoF + a] & (D - 1);
-                const float s = copysignf(0.5f, sign[m * twoF + a]);
+                const float s = copysignf(1.0f, sign[m * twoF + a]);   // increments arrive halved
                 const float v0 = row0[m * twoF + a];
                 const float v1 = two ? row1[m * twoF + a] : 0.f;
                 atomicAdd(&buf0[h].x, s * v0);
@@ -119,6 +120,53 @@ __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
     }
 }
 
+// hash/sign of every (level, coordinate) packed for the tuned kernel: float offset of the
+// bucket's real part inside a padded LDS slot, sign in bit 31.
+__global__ void pack_tables_kernel(const int32_t *hash, const float *sign, int64_t count, int D, uint32_t *table)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    const int h = hash[i] & (D - 1);
+    table[i] = (uint32_t)(tuned::pad(h) * 2) | (__float_as_uint(sign[i]) & 0x80000000u);
+}
+
+template <int LOG2D, int M>
+hipError_t launch_tuned(const float *dphi, const uint32_t *table, int64_t n_seq, int64_t L, int F,
+                        float *out, int64_t ld_out, hipStream_t stream)
+{
+    using P = tuned::Plan<LOG2D>;
+    const size_t lds = sizeof(float2) * (size_t)M * P::FPW * P::PD;
+    auto kernel = tuned::sketch_fft_scan_kernel<LOG2D, M>;
+    if (lds > 64 * 1024) {
+        static bool raised = false;
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL(kernel, dim3((unsigned)n_seq), dim3(64 * M), lds, stream, dphi, table, L, F, out, ld_out);
+    return hipGetLastError();
+}
+
+template <int LOG2D>
+hipError_t dispatch_levels(int M, const float *dphi, const uint32_t *table, int64_t n_seq, int64_t L, int F,
+                           float *out, int64_t ld_out, hipStream_t stream)
+{
+    switch (M) {
+        case 1: return launch_tuned<LOG2D, 1>(dphi, table, n_seq, L, F, out, ld_out, stream);
+        case 2: return launch_tuned<LOG2D, 2>(dphi, table, n_seq, L, F, out, ld_out, stream);
+        case 3: return launch_tuned<LOG2D, 3>(dphi, table, n_seq, L, F, out, ld_out, stream);
+        case 4: return launch_tuned<LOG2D, 4>(dphi, table, n_seq, L, F, out, ld_out, stream);
+        case 5: return launch_tuned<LOG2D, 5>(dphi, table, n_seq, L, F, out, ld_out, stream);
+        case 6: return launch_tuned<LOG2D, 6>(dphi, table, n_seq, L, F, out, ld_out, stream);
+        case 7: return launch_tuned<LOG2D, 7>(dphi, table, n_seq, L, F, out, ld_out, stream);
+        case 8: return launch_tuned<LOG2D, 8>(dphi, table, n_seq, L, F, out, ld_out, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 __global__ void fill_trivial_kernel(float *out, int64_t n_seq, int64_t ld_out, int64_t ncols)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -142,13 +190,34 @@ size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D)
     return (size_t)n_seq * (size_t)M * (size_t)(D / 2 + 1) * sizeof(float2);
 }
 
+bool sketch_fft_scan_is_tuned(int M, int D) { return M <= 8 && D >= 64 && D <= 2048; }
+
+hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int F, int D, uint32_t *table,
+                              hipStream_t stream)
+{
+    const int64_t count = (int64_t)M * 2 * F;
+    hipLaunchKernelGGL(pack_tables_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream,
+                       hash, sign, count, D, table);
+    return hipGetLastError();
+}
+
 hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
-                                  int64_t n_seq, int64_t L, int M, int F, int D,
+                                  const uint32_t *table, int64_t n_seq, int64_t L, int M, int F, int D,
                                   float *out, int64_t ld_out, float *state, hipStream_t stream)
 {
     if (n_seq == 0) return hipSuccess;
     int log2D = 0;
     while ((1 << log2D) < D) ++log2D;
+    if (sketch_fft_scan_is_tuned(M, D)) {
+        switch (log2D) {
+            case 6: return dispatch_levels<6>(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+            case 7: return dispatch_levels<7>(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+            case 8: return dispatch_levels<8>(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+            case 9: return dispatch_levels<9>(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+            case 10: return dispatch_levels<10>(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+            default: return dispatch_levels<11>(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+        }
+    }
     const size_t lds = sizeof(float2) * (size_t)(2 * D + D / 2 + 2 * (D / 2 + 1));
     static size_t lds_granted = 0;        // per process; raising the limit is idempotent
     if (lds > 64 * 1024 && lds > lds_granted) {

@@ -1,0 +1,306 @@
+// Tuned kernel for steps 3-4 (CountSketch, Fourier-domain level recursion over time, inverse
+// transform; Sec. 3.5, eqs. (cs), (ts_def), (ts_rec) with p = 1).
+//
+// Work decomposition (one workgroup per sequence, M wavefronts, wavefront m owns level m):
+//   per iteration every wavefront handles FPW pairs of consecutive time steps of its level:
+//     1. clears its LDS slots and scatter-adds the signed increments of the 2*FPW time steps
+//        into them (ds_add_f32; conflicts are resolved by the LDS atomics; step 2k goes to
+//        the real parts, step 2k+1 to the imaginary parts of slot k),
+//     2. runs FPW complex FFTs of length D held in its own LDS slots, G = D/R lanes per
+//        transform with R points per lane in registers (Stockham passes, radix up to 32 in
+//        registers, one LDS exchange per pass, no workgroup barrier inside the transform),
+//   then, after one barrier, every thread owns a few frequency bins, separates the two real
+//   transforms of each slot, and advances the accumulators A_1..A_M of its bins by the two
+//   time steps (A_m += A_{m-1}(before the step) * C_m, A_0 = 1).
+//   After the last time step, wavefront m transforms A_m back and writes block m of the row.
+//
+// The increments arrive pre-multiplied by 1/2 (done by the producing kernel), which is the
+// factor of the two-for-one separation  C0 = (Z[f] + conj Z[D-f]) / 2,  C1 = (Z[f] - conj Z[D-f]) / 2i.
+#pragma once
+
+#include "rfsf_internal.h"
+
+namespace rfsf {
+namespace tuned {
+
+// LDS index padding: one float2 of padding after every 16, so that the strided exchange of the
+// Stockham passes and the contiguous accesses are both free of bank conflicts.
+__host__ __device__ constexpr int pad(int e) { return e + (e >> 4); }
+
+template <int LOG2D_>
+struct Plan {
+    static constexpr int LOG2D = LOG2D_;
+    static constexpr int D = 1 << LOG2D;
+    static constexpr int LOG2R = (LOG2D == 9 || LOG2D == 11) ? 5 : 4;
+    static constexpr int R = 1 << LOG2R;        // points per lane
+    static constexpr int G = D / R;             // lanes per transform
+    static constexpr int FPW = 64 / G;          // transforms per wavefront
+    static constexpr int PD = D + D / 16;       // padded slot length in float2
+    static constexpr int NP = LOG2D <= 4 ? 1 : (LOG2D <= 9 ? 2 : 3);
+    static constexpr int radix(int p)
+    {
+        switch (LOG2D) {
+            case 4: return 16;
+            case 5: return p == 0 ? 16 : 2;
+            case 6: return p == 0 ? 16 : 4;
+            case 7: return p == 0 ? 16 : 8;
+            case 8: return 16;
+            case 9: return p == 0 ? 32 : 16;
+            case 10: return p < 2 ? 16 : 4;
+            default: return p < 2 ? 16 : 8;     // 11
+        }
+    }
+    static constexpr int Ns(int p) { return p == 0 ? 1 : Ns(p - 1) * radix(p - 1); }
+    // register-array offsets of pass p: twiddles (complex) and write bases
+    static constexpr int tw_off(int p) { return p <= 1 ? 0 : tw_off(p - 1) + (R / radix(p - 1)) * (radix(p - 1) - 1); }
+    static constexpr int wb_off(int p) { return p == 0 ? 0 : wb_off(p - 1) + R / radix(p - 1); }
+    static constexpr int NTW = NP == 1 ? 1 : tw_off(NP);
+    static constexpr int NWB = wb_off(NP);
+    static constexpr int roff(int q) { return G >= 16 ? q * (G + G / 16) : pad(G * q); }
+};
+
+// cos(k pi / 16), k = 0..8
+__device__ constexpr float kCos16[9] = {1.0f, 0.98078528040323043f, 0.92387953251128674f, 0.83146961230254524f,
+                                        0.70710678118654752f, 0.55557023301960218f, 0.38268343236508977f,
+                                        0.19509032201612825f, 0.0f};
+constexpr float cos_pi16(int k) { return k <= 8 ? kCos16[k] : -kCos16[16 - k]; }   // k in [0, 16]
+constexpr float sin_pi16(int k) { return k <= 8 ? kCos16[8 - k] : kCos16[k - 8]; }
+
+constexpr int bitrev(int x, int bits)
+{
+    int r = 0;
+    for (int i = 0; i < bits; ++i) r |= ((x >> i) & 1) << (bits - 1 - i);
+    return r;
+}
+constexpr int ilog2(int n) { return n <= 1 ? 0 : 1 + ilog2(n / 2); }
+
+// In-register forward DFT of N = 2..32 points, decimation in frequency; result k is left at
+// position bitrev(k). Twiddles are compile-time constants; the trivial ones cost nothing.
+template <int N, int BASE, int TOTAL>
+__device__ __forceinline__ void dft_dif(float2 (&x)[TOTAL])
+{
+    if constexpr (N >= 2) {
+        constexpr int H = N / 2;
+#pragma unroll
+        for (int i = 0; i < H; ++i) {
+            const float2 a = x[BASE + i], b = x[BASE + i + H];
+            x[BASE + i] = make_float2(a.x + b.x, a.y + b.y);
+            const float dx = a.x - b.x, dy = a.y - b.y;
+            const int k = i * (32 / N);                     // angle = k * pi / 16, k in [0, 16)
+            if (k == 0) {
+                x[BASE + i + H] = make_float2(dx, dy);
+            } else if (k == 8) {                             // times -i
+                x[BASE + i + H] = make_float2(dy, -dx);
+            } else if (k == 4) {                             // times (1 - i) / sqrt 2
+                x[BASE + i + H] = make_float2((dx + dy) * kCos16[4], (dy - dx) * kCos16[4]);
+            } else if (k == 12) {                            // times (-1 - i) / sqrt 2
+                x[BASE + i + H] = make_float2((dy - dx) * kCos16[4], -(dx + dy) * kCos16[4]);
+            } else {                                         // times (c - i s)
+                const float c = cos_pi16(k), s = sin_pi16(k);
+                x[BASE + i + H] = make_float2(fmaf(dx, c, dy * s), fmaf(dy, c, -dx * s));
+            }
+        }
+        dft_dif<H, BASE, TOTAL>(x);
+        dft_dif<H, BASE + H, TOTAL>(x);
+    }
+}
+
+__device__ __forceinline__ float2 cmulf(float2 a, float2 b)
+{
+    return make_float2(fmaf(a.x, b.x, -a.y * b.y), fmaf(a.x, b.y, a.y * b.x));
+}
+__device__ __forceinline__ float2 cfmaf(float2 a, float2 b, float2 c)   // a * b + c
+{
+    return make_float2(fmaf(a.x, b.x, fmaf(-a.y, b.y, c.x)), fmaf(a.x, b.y, fmaf(a.y, b.x, c.y)));
+}
+
+// Orders the LDS traffic of one wavefront: its LDS instructions execute in order, so only the
+// compiler has to be kept from moving accesses across this point.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Per-lane constants of the wavefront-local FFT.
+template <typename P>
+struct WaveFft {
+    float2 tw[P::NTW];
+    int wbase[P::NWB];
+    int rbase;
+
+    __device__ __forceinline__ void init(int lg)
+    {
+        rbase = pad(lg);
+        init_pass<0>(lg);
+    }
+
+    template <int PI>
+    __device__ __forceinline__ void init_pass(int lg)
+    {
+        if constexpr (PI < P::NP) {
+            constexpr int r = P::radix(PI), Ns = P::Ns(PI), NB = P::R / r;
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const int j = lg + P::G * u;
+                const int k = j & (Ns - 1);
+                wbase[P::wb_off(PI) + u] = pad((j - k) * r + k);
+                if constexpr (PI > 0) {
+#pragma unroll
+                    for (int t = 1; t < r; ++t) {
+                        float s, c;
+                        sincospif(-2.0f * (float)(k * t) / (float)(Ns * r), &s, &c);
+                        tw[P::tw_off(PI) + u * (r - 1) + (t - 1)] = make_float2(c, s);
+                    }
+                }
+            }
+            init_pass<PI + 1>(lg);
+        }
+    }
+
+    // Forward transform of the slot at `slot` (float2 LDS pointer, padded, natural order in and out).
+    __device__ __forceinline__ void run(float2 *slot) const
+    {
+        float2 v[P::R];
+#pragma unroll
+        for (int q = 0; q < P::R; ++q) v[q] = slot[rbase + P::roff(q)];
+        run_pass<0>(slot, v);
+    }
+
+    template <int PI>
+    __device__ __forceinline__ void run_pass(float2 *slot, float2 (&v)[P::R]) const
+    {
+        if constexpr (PI < P::NP) {
+            constexpr int r = P::radix(PI), Ns = P::Ns(PI), NB = P::R / r, LR = ilog2(r);
+            wave_lds_fence();                    // every lane has its inputs in registers
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                float2 x[r];
+#pragma unroll
+                for (int t = 0; t < r; ++t) {
+                    x[t] = v[u + t * NB];
+                    if constexpr (PI > 0) {
+                        if (t > 0) x[t] = cmulf(x[t], tw[P::tw_off(PI) + u * (r - 1) + (t - 1)]);
+                    }
+                }
+                dft_dif<r, 0, r>(x);
+                float2 *dst = slot + wbase[P::wb_off(PI) + u];
+#pragma unroll
+                for (int t = 0; t < r; ++t) dst[pad(t * Ns)] = x[bitrev(t, LR)];
+            }
+            wave_lds_fence();
+            if constexpr (PI + 1 < P::NP) {
+#pragma unroll
+                for (int q = 0; q < P::R; ++q) v[q] = slot[rbase + P::roff(q)];
+                run_pass<PI + 1>(slot, v);
+            }
+        }
+    }
+};
+
+template <int LOG2D, int M>
+__global__ __launch_bounds__(64 * M) void sketch_fft_scan_kernel(
+    const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L, int F,
+    float *__restrict__ out, int64_t ld_out)
+{
+    using P = Plan<LOG2D>;
+    constexpr int D = P::D, NT = 64 * M, NB = D / 2 + 1, BPT = (NB + NT - 1) / NT;
+    extern __shared__ float2 lds[];                    // [M][FPW][PD]
+    const int tid = threadIdx.x, lane = tid & 63, m = tid >> 6;
+    const int slot_id = lane / P::G, lg = lane % P::G;
+    float2 *wave_lds = lds + (size_t)m * P::FPW * P::PD;
+    float2 *my_slot = wave_lds + slot_id * P::PD;
+    const int64_t n = blockIdx.x, T = L - 1;
+    const int twoF = 2 * F;
+    const int64_t rf = (int64_t)M * twoF;
+    const float *seq = dphi + n * L * rf + (int64_t)m * twoF;   // row k of this level: seq + k * rf
+    const uint32_t *tab = table + (int64_t)m * twoF;
+
+    WaveFft<P> fft;
+    fft.init(lg);
+
+    float2 A[BPT][M];
+#pragma unroll
+    for (int b = 0; b < BPT; ++b)
+#pragma unroll
+        for (int l = 0; l < M; ++l) A[b][l] = make_float2(0.f, 0.f);
+
+    const int64_t pairs = (T + 1) / 2;
+    for (int64_t pair0 = 0; pair0 < pairs; pair0 += P::FPW) {
+        // 1. clear this wavefront's slots, then signed scatter-add of 2*FPW time steps
+        for (int i = lane; i < P::FPW * P::PD; i += 64) wave_lds[i] = make_float2(0.f, 0.f);
+        wave_lds_fence();
+        for (int a = lane; a < twoF; a += 64) {
+            const uint32_t t = tab[a];
+            const uint32_t sgn = t & 0x80000000u;
+            float *dst = reinterpret_cast<float *>(wave_lds) + (t & 0x7fffffffu);
+#pragma unroll
+            for (int s = 0; s < P::FPW; ++s) {
+                const int64_t k0 = 2 * (pair0 + s);
+                if (k0 < T) {
+                    const float v0 = __uint_as_float(__float_as_uint(seq[k0 * rf + a]) ^ sgn);
+                    atomicAdd(dst + s * (2 * P::PD), v0);
+                    if (k0 + 1 < T) {
+                        const float v1 = __uint_as_float(__float_as_uint(seq[(k0 + 1) * rf + a]) ^ sgn);
+                        atomicAdd(dst + s * (2 * P::PD) + 1, v1);
+                    }
+                }
+            }
+        }
+        // 2. FPW transforms per wavefront (run() starts with the intra-wavefront fence)
+        wave_lds_fence();
+        fft.run(my_slot);
+        __syncthreads();
+        // 3. per-bin separation and recurrence, two time steps per slot, levels ascending
+#pragma unroll
+        for (int s = 0; s < P::FPW; ++s) {
+#pragma unroll
+            for (int b = 0; b < BPT; ++b) {
+                const int f = tid + NT * b;
+                if (f < NB) {
+                    const int fi = pad(f), fc = pad((D - f) & (D - 1));
+                    float2 p0 = make_float2(1.f, 0.f), p1 = make_float2(1.f, 0.f);
+#pragma unroll
+                    for (int l = 0; l < M; ++l) {
+                        const float2 *Z = lds + ((size_t)l * P::FPW + s) * P::PD;
+                        const float2 z = Z[fi], zc = Z[fc];
+                        const float2 C0 = make_float2(z.x + zc.x, z.y - zc.y);
+                        const float2 C1 = make_float2(z.y + zc.y, zc.x - z.x);
+                        const float2 a_old = A[b][l];
+                        const float2 a_mid = cfmaf(p0, C0, a_old);
+                        A[b][l] = cfmaf(p1, C1, a_mid);
+                        p0 = a_old;
+                        p1 = a_mid;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // Phi_m = Re(FFT(conj Y_m)) / D with Y_m the Hermitian extension of A_m; slot 0 of wavefront m.
+#pragma unroll
+    for (int b = 0; b < BPT; ++b) {
+        const int f = tid + NT * b;
+        if (f < NB) {
+#pragma unroll
+            for (int l = 0; l < M; ++l) {
+                float2 *Y = lds + (size_t)l * P::FPW * P::PD;
+                const float2 y = A[b][l];
+                Y[pad(f)] = make_float2(y.x, -y.y);
+                if (f > 0 && f < D / 2) Y[pad(D - f)] = y;
+            }
+        }
+    }
+    __syncthreads();
+    fft.run(my_slot);
+    wave_lds_fence();
+    float *row = out + n * ld_out;
+    if (tid == 0) row[0] = 1.0f;
+    const float invD = 1.0f / (float)D;
+    for (int j = lane; j < D; j += 64) row[1 + (int64_t)m * D + j] = wave_lds[pad(j)].x * invD;
+}
+
+}  // namespace tuned
+}  // namespace rfsf

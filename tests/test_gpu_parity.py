@@ -67,6 +67,11 @@ def test_small_64_rows(oracle):
     (2, 20, 4, 2, 8, 4096),     # largest D
     (3, 300, 33, 3, 130, 512),  # d above one MFMA K-slab, F with a ragged column tile
     (1, 1000, 2, 5, 16, 8),     # long and narrow
+    (3, 24, 6, 5, 100, 1024),   # D = 1024, three-pass transform
+    (2, 11, 4, 2, 300, 2048),   # D = 2048, 32 points per lane
+    (2, 40, 3, 8, 20, 256),     # eight levels
+    (2, 30, 3, 9, 12, 64),      # nine levels: generic kernel
+    (3, 50, 5, 7, 33, 128),     # seven levels, D = 128
 ])
 def test_ragged_shapes(oracle, N, L, d, M, F, D):
     inp = _random_case(100 + N + L + D, N, L, d, M, F, D)
