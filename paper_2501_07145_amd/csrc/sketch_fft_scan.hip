@@ -120,14 +120,20 @@ __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
     }
 }
 
-// hash/sign of every (level, coordinate) packed for the tuned kernel: float offset of the
-// bucket's real part inside a padded LDS slot, sign in bit 31.
-__global__ void pack_tables_kernel(const int32_t *hash, const float *sign, int64_t count, int D, uint32_t *table)
+// hash/sign of every (level, coordinate) packed for the tuned kernel (layout: see kSkipEntry).
+// The collision level counts the earlier coordinates of the same aligned group of 64 (within
+// the level's own 2F coordinates) that fall into the same bucket.
+__global__ void pack_tables_kernel(const int32_t *hash, const float *sign, int M, int twoF, int D, uint32_t *table)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= count) return;
+    if (i >= (int64_t)M * twoF) return;
+    const int a = (int)(i % twoF);
+    const int64_t base = i - a;
     const int h = hash[i] & (D - 1);
-    table[i] = (uint32_t)(tuned::pad(h) * 2) | (__float_as_uint(sign[i]) & 0x80000000u);
+    int level = 0;
+    for (int a2 = a & ~63; a2 < a; ++a2) level += (hash[base + a2] & (D - 1)) == h;
+    if (level > 2) level = 2;
+    table[i] = (uint32_t)tuned::pad(h) | ((uint32_t)level << 16) | (__float_as_uint(sign[i]) & 0x80000000u);
 }
 
 template <int LOG2D, int M>
@@ -135,7 +141,7 @@ hipError_t launch_tuned(const float *dphi, const uint32_t *table, int64_t n_seq,
                         float *out, int64_t ld_out, hipStream_t stream)
 {
     using P = tuned::Plan<LOG2D>;
-    const size_t lds = sizeof(float2) * (size_t)M * P::FPW * P::PD;
+    const size_t lds = sizeof(float2) * (size_t)M * P::FPW * P::PS;
     auto kernel = tuned::sketch_fft_scan_kernel<LOG2D, M>;
     if (lds > 64 * 1024) {
         static bool raised = false;
@@ -197,7 +203,7 @@ hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int
 {
     const int64_t count = (int64_t)M * 2 * F;
     hipLaunchKernelGGL(pack_tables_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream,
-                       hash, sign, count, D, table);
+                       hash, sign, M, 2 * F, D, table);
     return hipGetLastError();
 }
 

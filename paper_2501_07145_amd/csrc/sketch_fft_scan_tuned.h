@@ -4,8 +4,13 @@
 // Work decomposition (one workgroup per sequence, M wavefronts, wavefront m owns level m):
 //   per iteration every wavefront handles FPW pairs of consecutive time steps of its level:
 //     1. clears its LDS slots and scatter-adds the signed increments of the 2*FPW time steps
-//        into them (ds_add_f32; conflicts are resolved by the LDS atomics; step 2k goes to
-//        the real parts, step 2k+1 to the imaginary parts of slot k),
+//        into them (step 2k goes to the real parts, step 2k+1 to the imaginary parts of slot
+//        k). LDS float atomics cost about three cycles per lane on this chip, so conflicts are
+//        handled wavefront-locally instead: the 2F coordinates are taken 64 at a time; a
+//        precomputed level says how many earlier coordinates of the same 64 share the bucket.
+//        Level-0 lanes hit distinct buckets and do a plain read-add-write, level-1 lanes do
+//        the same in a second masked round, and only the rare deeper collisions use ds_add_f32.
+//        Successive groups of 64 are ordered by the in-order LDS queue of the wavefront,
 //     2. runs FPW complex FFTs of length D held in its own LDS slots, G = D/R lanes per
 //        transform with R points per lane in registers (Stockham passes, radix up to 32 in
 //        registers, one LDS exchange per pass, no workgroup barrier inside the transform),
@@ -35,7 +40,9 @@ struct Plan {
     static constexpr int R = 1 << LOG2R;        // points per lane
     static constexpr int G = D / R;             // lanes per transform
     static constexpr int FPW = 64 / G;          // transforms per wavefront
-    static constexpr int PD = D + D / 16;       // padded slot length in float2
+    static constexpr int PD = D + D / 16;       // padded transform length in float2
+    static constexpr int PS = PD + 64;          // slot stride: one spare float2 per lane behind the data
+    static constexpr int LOADB = FPW >= 16 ? 1 : 16 / FPW;   // 64-coordinate groups loaded per batch
     static constexpr int NP = LOG2D <= 4 ? 1 : (LOG2D <= 9 ? 2 : 3);
     static constexpr int radix(int p)
     {
@@ -199,6 +206,11 @@ struct WaveFft {
     }
 };
 
+// Packed table entry: bits 0-15 float2 index of the bucket inside a padded slot, bits 16-17
+// collision level inside the group of 64 coordinates (0, 1, 2 = two or more earlier ones,
+// 3 = no coordinate), bit 31 the sign.
+constexpr uint32_t kSkipEntry = 3u << 16;
+
 template <int LOG2D, int M>
 __global__ __launch_bounds__(64 * M) void sketch_fft_scan_kernel(
     const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L, int F,
@@ -206,11 +218,11 @@ __global__ __launch_bounds__(64 * M) void sketch_fft_scan_kernel(
 {
     using P = Plan<LOG2D>;
     constexpr int D = P::D, NT = 64 * M, NB = D / 2 + 1, BPT = (NB + NT - 1) / NT;
-    extern __shared__ float2 lds[];                    // [M][FPW][PD]
+    extern __shared__ float2 lds[];                    // [M][FPW][PS]
     const int tid = threadIdx.x, lane = tid & 63, m = tid >> 6;
     const int slot_id = lane / P::G, lg = lane % P::G;
-    float2 *wave_lds = lds + (size_t)m * P::FPW * P::PD;
-    float2 *my_slot = wave_lds + slot_id * P::PD;
+    float2 *wave_lds = lds + (size_t)m * P::FPW * P::PS;
+    float2 *my_slot = wave_lds + slot_id * P::PS;
     const int64_t n = blockIdx.x, T = L - 1;
     const int twoF = 2 * F;
     const int64_t rf = (int64_t)M * twoF;
@@ -229,23 +241,58 @@ __global__ __launch_bounds__(64 * M) void sketch_fft_scan_kernel(
     const int64_t pairs = (T + 1) / 2;
     for (int64_t pair0 = 0; pair0 < pairs; pair0 += P::FPW) {
         // 1. clear this wavefront's slots, then signed scatter-add of 2*FPW time steps
-        for (int i = lane; i < P::FPW * P::PD; i += 64) wave_lds[i] = make_float2(0.f, 0.f);
+        for (int i = lane; i < P::FPW * P::PS; i += 64) wave_lds[i] = make_float2(0.f, 0.f);
         wave_lds_fence();
-        for (int a = lane; a < twoF; a += 64) {
-            const uint32_t t = tab[a];
-            const uint32_t sgn = t & 0x80000000u;
-            float *dst = reinterpret_cast<float *>(wave_lds) + (t & 0x7fffffffu);
+        for (int a0 = 0; a0 < twoF; a0 += 64 * P::LOADB) {
+            uint32_t tb[P::LOADB];
+            float2 val[P::LOADB][P::FPW];
+            // all global loads of the batch are issued before the first use
 #pragma unroll
-            for (int s = 0; s < P::FPW; ++s) {
-                const int64_t k0 = 2 * (pair0 + s);
-                if (k0 < T) {
-                    const float v0 = __uint_as_float(__float_as_uint(seq[k0 * rf + a]) ^ sgn);
-                    atomicAdd(dst + s * (2 * P::PD), v0);
-                    if (k0 + 1 < T) {
-                        const float v1 = __uint_as_float(__float_as_uint(seq[(k0 + 1) * rf + a]) ^ sgn);
-                        atomicAdd(dst + s * (2 * P::PD) + 1, v1);
+            for (int b = 0; b < P::LOADB; ++b) {
+                const int a = a0 + 64 * b + lane;
+                const bool ok = a < twoF;
+                const int aa = ok ? a : twoF - 1;
+                const uint32_t t = tab[aa];
+                tb[b] = ok ? t : kSkipEntry;
+                const uint32_t sgn = t & 0x80000000u;
+#pragma unroll
+                for (int s = 0; s < P::FPW; ++s) {
+                    const int64_t k0 = 2 * (pair0 + s);
+                    const int64_t kk0 = k0 < T ? k0 : T - 1, kk1 = k0 + 1 < T ? k0 + 1 : T - 1;
+                    const float x0 = __uint_as_float(__float_as_uint(seq[kk0 * rf + aa]) ^ sgn);
+                    const float x1 = __uint_as_float(__float_as_uint(seq[kk1 * rf + aa]) ^ sgn);
+                    val[b][s] = make_float2(k0 < T ? x0 : 0.f, k0 + 1 < T ? x1 : 0.f);
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < P::LOADB; ++b) {
+                const uint32_t lvl = (tb[b] >> 16) & 3u;
+                const int off = (int)(tb[b] & 0xffffu);
+                // round 0: every lane issues; lanes of other levels use their spare float2
+                const int sel = lvl == 0 ? off : P::PD + lane;
+                float2 old[P::FPW];
+#pragma unroll
+                for (int s = 0; s < P::FPW; ++s) old[s] = wave_lds[s * P::PS + sel];
+#pragma unroll
+                for (int s = 0; s < P::FPW; ++s)
+                    wave_lds[s * P::PS + sel] = make_float2(old[s].x + val[b][s].x, old[s].y + val[b][s].y);
+                wave_lds_fence();
+                if (lvl == 1) {                       // second coordinate of a bucket inside this group
+#pragma unroll
+                    for (int s = 0; s < P::FPW; ++s) old[s] = wave_lds[s * P::PS + off];
+#pragma unroll
+                    for (int s = 0; s < P::FPW; ++s)
+                        wave_lds[s * P::PS + off] = make_float2(old[s].x + val[b][s].x, old[s].y + val[b][s].y);
+                }
+                wave_lds_fence();
+                if (lvl == 2) {                       // third or later: rare, LDS float atomics
+#pragma unroll
+                    for (int s = 0; s < P::FPW; ++s) {
+                        atomicAdd(&wave_lds[s * P::PS + off].x, val[b][s].x);
+                        atomicAdd(&wave_lds[s * P::PS + off].y, val[b][s].y);
                     }
                 }
+                wave_lds_fence();
             }
         }
         // 2. FPW transforms per wavefront (run() starts with the intra-wavefront fence)
@@ -263,7 +310,7 @@ __global__ __launch_bounds__(64 * M) void sketch_fft_scan_kernel(
                     float2 p0 = make_float2(1.f, 0.f), p1 = make_float2(1.f, 0.f);
 #pragma unroll
                     for (int l = 0; l < M; ++l) {
-                        const float2 *Z = lds + ((size_t)l * P::FPW + s) * P::PD;
+                        const float2 *Z = lds + ((size_t)l * P::FPW + s) * P::PS;
                         const float2 z = Z[fi], zc = Z[fc];
                         const float2 C0 = make_float2(z.x + zc.x, z.y - zc.y);
                         const float2 C1 = make_float2(z.y + zc.y, zc.x - z.x);
@@ -286,7 +333,7 @@ __global__ __launch_bounds__(64 * M) void sketch_fft_scan_kernel(
         if (f < NB) {
 #pragma unroll
             for (int l = 0; l < M; ++l) {
-                float2 *Y = lds + (size_t)l * P::FPW * P::PD;
+                float2 *Y = lds + (size_t)l * P::FPW * P::PS;
                 const float2 y = A[b][l];
                 Y[pad(f)] = make_float2(y.x, -y.y);
                 if (f > 0 && f < D / 2) Y[pad(D - f)] = y;
