@@ -71,6 +71,91 @@ __global__ __launch_bounds__(256) void rff_increments_valu(
     }
 }
 
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// Matrix-core kernel (fp32 operands). A workgroup of four wavefronts owns 128 frequencies of
+// one level and a range of flattened rows; wavefront w owns frequencies 32w..32w+31. Per tile
+// of 32 rows, theta[32 rows x 32 freq] = X_tile[32 x d] * W[d x 32] is accumulated with
+// v_mfma_f32_32x32x2f32 (A = rows x channels from LDS, B = channels x frequencies held in
+// registers for the whole row range). In the result a lane holds one frequency (lane % 32)
+// and rows 8q + 4*(lane/32) + i, q,i = 0..3, so the time difference is local except at the
+// 4-row boundaries, where the two half-wavefronts exchange one value per block of rows.
+template <int KSTEPS>     // ceil(d / 2) padded: channels 2*KSTEPS
+__global__ __launch_bounds__(256) void rff_increments_mfma(
+    const float *__restrict__ X, const float *__restrict__ W, float inv_lengthscale, float scale,
+    int64_t rows, int d, int M, int F, int64_t rows_per_block, float *__restrict__ dphi)
+{
+    constexpr int KP = 2 * KSTEPS;              // padded channel count
+    constexpr int XS = KP | 1;                  // odd LDS row stride: conflict-free A reads
+    __shared__ float xs[kRowsPerTile * XS];
+    const int fblocks = (F + 127) / 128;
+    const int m = blockIdx.y / fblocks;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = lane >> 5, col = lane & 31;
+    const int f = (blockIdx.y % fblocks) * 128 + wave * 32 + col;     // this lane's frequency
+    const bool f_ok = f < F;
+    const int64_t g0 = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t g1 = min(rows - 1, g0 + rows_per_block);             // last row whose phi we need
+    const int64_t rf = (int64_t)M * 2 * F;
+
+    // B operand: W[m][k][f] for k = 2*kk + half, zero beyond d or F
+    float breg[KSTEPS];
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+        const int k = 2 * kk + half;
+        breg[kk] = (f_ok && k < d) ? W[((int64_t)m * d + k) * F + f] * inv_lengthscale : 0.f;
+    }
+    float carry_c = 0.f, carry_s = 0.f;         // row 31 of the previous tile (lower half-wavefront)
+    float *out_base = dphi + (int64_t)m * 2 * F + f;
+
+    for (int64_t gt = g0; gt <= g1; gt += kRowsPerTile) {
+        const int nrow = (int)min((int64_t)kRowsPerTile, g1 - gt + 1);
+        __syncthreads();
+        for (int i = threadIdx.x; i < kRowsPerTile * KP; i += 256) {
+            const int r = i / KP, c = i - r * KP;
+            xs[r * XS + c] = (r < nrow && c < d) ? X[(gt + r) * d + c] : 0.f;
+        }
+        __syncthreads();
+        floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xs[col * XS + 2 * kk + half], breg[kk], acc, 0, 0, 0);
+
+        float cs[16], sn[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            sincos_reduced(acc[v], sn[v], cs[v]);
+            cs[v] *= scale;
+            sn[v] *= scale;
+        }
+        // value of the row just above each 4-row block: from the partner half-wavefront
+        float up_c[4], up_s[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float pc = __shfl_xor(cs[4 * q + 3], 32);
+            const float ps = __shfl_xor(sn[4 * q + 3], 32);
+            // upper half needs rows 8q+3 (partner's block q); lower half needs rows 8q-1
+            // (partner's block q-1, or the previous tile for q = 0)
+            if (half) { up_c[q] = pc; up_s[q] = ps; }
+            else if (q < 3) { up_c[q + 1] = pc; up_s[q + 1] = ps; }
+            if (q == 3 && !half) { up_c[0] = carry_c; up_s[0] = carry_s; carry_c = pc; carry_s = ps; }
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 8 * (v >> 2) + 4 * half + (v & 3);
+            const float prev_c = (v & 3) ? cs[v - 1] : up_c[v >> 2];
+            const float prev_s = (v & 3) ? sn[v - 1] : up_s[v >> 2];
+            const int64_t g = gt + r;
+            if (f_ok && r < nrow && g > g0) {
+                float *dst = out_base + (g - 1) * rf;
+                dst[0] = cs[v] - prev_c;
+                dst[F] = sn[v] - prev_s;
+            }
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_rff_increments(const float *X, const float *W, float inv_lengthscale,
@@ -80,11 +165,25 @@ hipError_t launch_rff_increments(const float *X, const float *W, float inv_lengt
     (void)bf16;
     const int64_t rows = n_seq * L;
     if (rows < 2) return hipSuccess;
-    const int64_t rows_per_block = 256;
+    const int64_t rows_per_block = 255;     // 256 rows of phi = eight tiles; consecutive blocks share one row
     const int64_t nblk = (rows - 1 + rows_per_block - 1) / rows_per_block;
+    const float scale = 0.5f / sqrtf((float)F);    // the consumer's two-for-one FFT wants halved increments
+    if (d <= 64) {
+        const int fb = (F + 127) / 128;
+        dim3 grid((unsigned)nblk, (unsigned)(M * fb));
+#define RFSF_LAUNCH_MFMA(KS)                                                                              \
+    hipLaunchKernelGGL(rff_increments_mfma<KS>, grid, dim3(256), 0, stream, X, W, inv_lengthscale, scale, \
+                       rows, d, M, F, rows_per_block, dphi)
+        if (d <= 4) RFSF_LAUNCH_MFMA(2);
+        else if (d <= 8) RFSF_LAUNCH_MFMA(4);
+        else if (d <= 18) RFSF_LAUNCH_MFMA(9);
+        else if (d <= 32) RFSF_LAUNCH_MFMA(16);
+        else RFSF_LAUNCH_MFMA(32);
+#undef RFSF_LAUNCH_MFMA
+        return hipGetLastError();
+    }
     const int fblocks = (F + 255) / 256;
     dim3 grid((unsigned)nblk, (unsigned)(M * fblocks));
-    const float scale = 0.5f / sqrtf((float)F);    // the consumer's two-for-one FFT wants halved increments
     hipLaunchKernelGGL(rff_increments_valu, grid, dim3(256), sizeof(float) * kRowsPerTile * d, stream,
                        X, W, inv_lengthscale, scale, rows, d, M, F, rows_per_block, dphi);
     return hipGetLastError();
