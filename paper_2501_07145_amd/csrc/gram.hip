@@ -46,12 +46,133 @@ __global__ __launch_bounds__(256) void gram_generic(
         }
 }
 
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kKT = 32;             // K slab
+constexpr int kLdsStride = kKT + 4; // floats per LDS row: 16 consecutive rows start in distinct bank quads
+
+// Matrix-core kernel (v_mfma_f32_32x32x2f32). Workgroup tile (64*WT) x (64*WT), four wavefronts
+// in a 2x2 grid, each owning (32*WT) x (32*WT) as WT x WT blocks of 32x32. Both operands are
+// K-contiguous rows, staged per K slab of 32 through LDS with float4 loads; the next slab is
+// fetched into registers while the current one is multiplied.
+// MFMA k-step kk of a slab uses the physical columns kk (lanes 0-31) and kk + 16 (lanes 32-63),
+// the same for both operands, so that each lane reads 16 consecutive floats of its row.
+// Needs 16-byte aligned bases and leading dimensions that are multiples of 4.
+template <int WT>
+__global__ __launch_bounds__(256) void gram_mfma(
+    const float *__restrict__ A, int64_t Nx, int64_t lda, const float *__restrict__ B, int64_t Ny,
+    int64_t ldb, int64_t K, float *__restrict__ C, int64_t ldc)
+{
+    constexpr int TILE = 64 * WT;               // rows of A (and of B) per workgroup
+    constexpr int NLD = TILE * (kKT / 4) / 256; // float4 loads per thread per operand per slab
+    __shared__ float As[TILE * kLdsStride];
+    __shared__ float Bs[TILE * kLdsStride];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, col = lane & 31;
+    const int wi = wave >> 1, wj = wave & 1;
+    const int64_t i0 = (int64_t)blockIdx.y * TILE, j0 = (int64_t)blockIdx.x * TILE;
+
+    floatx16 acc[WT][WT];
+#pragma unroll
+    for (int a = 0; a < WT; ++a)
+#pragma unroll
+        for (int b = 0; b < WT; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    float4 ra[NLD], rb[NLD];
+    auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            const int e = tid + 256 * u;                 // float4 slot inside the slab tile
+            const int r = e / (kKT / 4), c4 = e % (kKT / 4);
+            const int64_t k = k0 + 4 * c4;
+            float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va;
+            if (k < K) {
+                if (i0 + r < Nx) va = *reinterpret_cast<const float4 *>(A + (i0 + r) * lda + k);
+                if (j0 + r < Ny) vb = *reinterpret_cast<const float4 *>(B + (j0 + r) * ldb + k);
+                if (k + 3 >= K) {                        // columns beyond K hold padding, not data
+                    if (k + 1 >= K) { va.y = 0.f; vb.y = 0.f; }
+                    if (k + 2 >= K) { va.z = 0.f; vb.z = 0.f; }
+                    va.w = 0.f; vb.w = 0.f;
+                }
+            }
+            ra[u] = va;
+            rb[u] = vb;
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            const int e = tid + 256 * u;
+            const int r = e / (kKT / 4), c4 = e % (kKT / 4);
+            *reinterpret_cast<float4 *>(&As[r * kLdsStride + 4 * c4]) = ra[u];
+            *reinterpret_cast<float4 *>(&Bs[r * kLdsStride + 4 * c4]) = rb[u];
+        }
+    };
+
+    fetch(0);
+    for (int64_t k0 = 0; k0 < K; k0 += kKT) {
+        __syncthreads();                                 // previous slab fully consumed
+        stage();
+        __syncthreads();
+        if (k0 + kKT < K) fetch(k0 + kKT);
+        // this lane's 16 columns of each of its rows: physical columns 16*half .. 16*half+15
+        float4 fa[WT][4], fb[WT][4];
+#pragma unroll
+        for (int t = 0; t < WT; ++t)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                fa[t][c] = *reinterpret_cast<const float4 *>(&As[((wi * WT + t) * 32 + col) * kLdsStride + 16 * half + 4 * c]);
+                fb[t][c] = *reinterpret_cast<const float4 *>(&Bs[((wj * WT + t) * 32 + col) * kLdsStride + 16 * half + 4 * c]);
+            }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int a = 0; a < WT; ++a)
+#pragma unroll
+                    for (int b = 0; b < WT; ++b) {
+                        const float av = e == 0 ? fa[a][c].x : e == 1 ? fa[a][c].y : e == 2 ? fa[a][c].z : fa[a][c].w;
+                        const float bv = e == 0 ? fb[b][c].x : e == 1 ? fb[b][c].y : e == 2 ? fb[b][c].z : fb[b][c].w;
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[a][b], 0, 0, 0);
+                    }
+    }
+    // result layout of a 32x32 block: lane holds column lane%32 and rows 8q + 4*(lane/32) + i
+#pragma unroll
+    for (int a = 0; a < WT; ++a)
+#pragma unroll
+        for (int b = 0; b < WT; ++b) {
+            const int64_t j = j0 + (wj * WT + b) * 32 + col;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t i = i0 + (wi * WT + a) * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                if (i < Nx && j < Ny) C[i * ldc + j] = acc[a][b][v];
+            }
+        }
+}
+
 }  // namespace
 
 hipError_t launch_gram(const float *PhiX, int64_t Nx, int64_t ldx, const float *PhiY, int64_t Ny,
                        int64_t ldy, int64_t ncols, float *K, int64_t ldk, hipStream_t stream)
 {
     if (Nx == 0 || Ny == 0) return hipSuccess;
+    const bool aligned = ldx % 4 == 0 && ldy % 4 == 0 && reinterpret_cast<uintptr_t>(PhiX) % 16 == 0 &&
+                         reinterpret_cast<uintptr_t>(PhiY) % 16 == 0;
+    if (aligned) {
+        const int64_t big_tiles = ((Nx + 127) / 128) * ((Ny + 127) / 128);
+        if (big_tiles >= 512) {
+            dim3 g((unsigned)((Ny + 127) / 128), (unsigned)((Nx + 127) / 128));
+            hipLaunchKernelGGL(gram_mfma<2>, g, dim3(256), 0, stream, PhiX, Nx, ldx, PhiY, Ny, ldy, ncols, K, ldk);
+        } else {
+            dim3 g((unsigned)((Ny + 63) / 64), (unsigned)((Nx + 63) / 64));
+            hipLaunchKernelGGL(gram_mfma<1>, g, dim3(256), 0, stream, PhiX, Nx, ldx, PhiY, Ny, ldy, ncols, K, ldk);
+        }
+        return hipGetLastError();
+    }
     dim3 grid((unsigned)((Ny + kTile - 1) / kTile), (unsigned)((Nx + kTile - 1) / kTile));
     hipLaunchKernelGGL(gram_generic, grid, dim3(256), 0, stream, PhiX, Nx, ldx, PhiY, Ny, ldy, ncols, K, ldk);
     return hipGetLastError();
