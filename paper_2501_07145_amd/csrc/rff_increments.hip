@@ -156,18 +156,130 @@ __global__ __launch_bounds__(256) void rff_increments_mfma(
     }
 }
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// float -> bfloat16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t bf16_bits(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ float bf16_value(uint32_t b) { return __uint_as_float(b << 16); }
+
+// Matrix-core kernel with bf16 operands and fp32 accumulation (v_mfma_f32_32x32x16_bf16).
+// W is rounded to bf16; X is split into two bf16 terms, hi = bf16(x) and lo = bf16(x - hi),
+// and both are multiplied with the same W, so that the time difference of the angles does not
+// inherit the 2^-9 rounding of x itself. Same tiling and epilogue as the fp32 kernel.
+template <int KSTEPS>     // ceil(d / 16): channels padded to 16*KSTEPS
+__global__ __launch_bounds__(256) void rff_increments_mfma_bf16(
+    const float *__restrict__ X, const float *__restrict__ W, float inv_lengthscale, float scale,
+    int64_t rows, int d, int M, int F, int64_t rows_per_block, float *__restrict__ dphi)
+{
+    constexpr int KP = 16 * KSTEPS;
+    constexpr int XS = KP + 8;                  // bf16 elements per LDS row (16-byte padded)
+    __shared__ __attribute__((aligned(16))) uint16_t xhi[kRowsPerTile * XS];
+    __shared__ __attribute__((aligned(16))) uint16_t xlo[kRowsPerTile * XS];
+    const int fblocks = (F + 127) / 128;
+    const int m = blockIdx.y / fblocks;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = lane >> 5, col = lane & 31;
+    const int f = (blockIdx.y % fblocks) * 128 + wave * 32 + col;
+    const bool f_ok = f < F;
+    const int64_t g0 = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t g1 = min(rows - 1, g0 + rows_per_block);
+    const int64_t rf = (int64_t)M * 2 * F;
+
+    // B operand: lane holds W[m][16*kk + 8*half + e][f], e = 0..7, as bf16
+    bf16x8 breg[KSTEPS];
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const int k = 16 * kk + 8 * half + e;
+            const float w0 = (f_ok && k < d) ? W[((int64_t)m * d + k) * F + f] : 0.f;
+            const float w1 = (f_ok && k + 1 < d) ? W[((int64_t)m * d + k + 1) * F + f] : 0.f;
+            w[e / 2] = bf16_bits(w0) | (bf16_bits(w1) << 16);
+        }
+        breg[kk] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+    }
+    float carry_c = 0.f, carry_s = 0.f;
+    float *out_base = dphi + (int64_t)m * 2 * F + f;
+
+    for (int64_t gt = g0; gt <= g1; gt += kRowsPerTile) {
+        const int nrow = (int)min((int64_t)kRowsPerTile, g1 - gt + 1);
+        __syncthreads();
+        for (int i = threadIdx.x; i < kRowsPerTile * KP; i += 256) {
+            const int r = i / KP, c = i - r * KP;
+            const float x = (r < nrow && c < d) ? X[(gt + r) * d + c] : 0.f;
+            const uint32_t hi = bf16_bits(x);
+            xhi[r * XS + c] = (uint16_t)hi;
+            xlo[r * XS + c] = (uint16_t)bf16_bits(x - bf16_value(hi));
+        }
+        __syncthreads();
+        floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&xhi[col * XS + 16 * kk + 8 * half]));
+            const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&xlo[col * XS + 16 * kk + 8 * half]));
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, breg[kk], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, breg[kk], acc, 0, 0, 0);
+        }
+        float cs[16], sn[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            sincos_reduced(acc[v] * inv_lengthscale, sn[v], cs[v]);
+            cs[v] *= scale;
+            sn[v] *= scale;
+        }
+        float up_c[4], up_s[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float pc = __shfl_xor(cs[4 * q + 3], 32);
+            const float ps = __shfl_xor(sn[4 * q + 3], 32);
+            if (half) { up_c[q] = pc; up_s[q] = ps; }
+            else if (q < 3) { up_c[q + 1] = pc; up_s[q + 1] = ps; }
+            if (q == 3 && !half) { up_c[0] = carry_c; up_s[0] = carry_s; carry_c = pc; carry_s = ps; }
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 8 * (v >> 2) + 4 * half + (v & 3);
+            const float prev_c = (v & 3) ? cs[v - 1] : up_c[v >> 2];
+            const float prev_s = (v & 3) ? sn[v - 1] : up_s[v >> 2];
+            const int64_t g = gt + r;
+            if (f_ok && r < nrow && g > g0) {
+                float *dst = out_base + (g - 1) * rf;
+                dst[0] = cs[v] - prev_c;
+                dst[F] = sn[v] - prev_s;
+            }
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_rff_increments(const float *X, const float *W, float inv_lengthscale,
                                  int64_t n_seq, int64_t L, int d, int M, int F, bool bf16,
                                  float *dphi, hipStream_t stream)
 {
-    (void)bf16;
     const int64_t rows = n_seq * L;
     if (rows < 2) return hipSuccess;
     const int64_t rows_per_block = 255;     // 256 rows of phi = eight tiles; consecutive blocks share one row
     const int64_t nblk = (rows - 1 + rows_per_block - 1) / rows_per_block;
     const float scale = 0.5f / sqrtf((float)F);    // the consumer's two-for-one FFT wants halved increments
+    if (bf16) {            // the caller (API layer) has checked d <= 128
+        const int fb = (F + 127) / 128;
+        dim3 grid((unsigned)nblk, (unsigned)(M * fb));
+#define RFSF_LAUNCH_BF16(KS)                                                                                   \
+    hipLaunchKernelGGL(rff_increments_mfma_bf16<KS>, grid, dim3(256), 0, stream, X, W, inv_lengthscale, scale, \
+                       rows, d, M, F, rows_per_block, dphi)
+        if (d <= 16) RFSF_LAUNCH_BF16(1);
+        else if (d <= 32) RFSF_LAUNCH_BF16(2);
+        else if (d <= 64) RFSF_LAUNCH_BF16(4);
+        else RFSF_LAUNCH_BF16(8);
+#undef RFSF_LAUNCH_BF16
+        return hipGetLastError();
+    }
     if (d <= 64) {
         const int fb = (F + 127) / 128;
         dim3 grid((unsigned)nblk, (unsigned)(M * fb));

@@ -128,6 +128,7 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
                    ? RFSF_OK : RFSF_E_HIP;
     }
     if ((int64_t)shape->M * ((shape->F + 127) / 128) > 65535) return RFSF_E_UNSUPPORTED;
+    if (shape->rff_bf16 != 0 && shape->d > 128) return RFSF_E_UNSUPPORTED;
     if (!workspace) return RFSF_E_NULLPTR;
     int64_t chunk = chunk_for(shape, workspace_bytes);
     if (chunk < 1) return RFSF_E_WORKSPACE_TOO_SMALL;

@@ -8,8 +8,8 @@
 //        k). LDS float atomics cost about three cycles per lane on this chip, so conflicts are
 //        handled wavefront-locally instead: the 2F coordinates are taken 64 at a time; a
 //        precomputed level says how many earlier coordinates of the same 64 share the bucket.
-//        Level-0 lanes hit distinct buckets and do a plain read-add-write, level-1 lanes do
-//        the same in a second masked round, and only the rare deeper collisions use ds_add_f32.
+//        Level-0 lanes hit distinct buckets and do a plain read-add-write; for D <= 512 the
+//        level-1 lanes do the same in a second masked round; the rare rest uses ds_add_f32.
 //        Successive groups of 64 are ordered by the in-order LDS queue of the wavefront,
 //     2. runs FPW complex FFTs of length D held in its own LDS slots, G = D/R lanes per
 //        transform with R points per lane in registers (Stockham passes, radix up to 32 in
@@ -42,7 +42,7 @@ struct Plan {
     static constexpr int FPW = 64 / G;          // transforms per wavefront
     static constexpr int PD = D + D / 16;       // padded transform length in float2
     static constexpr int PS = PD + 64;          // slot stride: one spare float2 per lane behind the data
-    static constexpr int LOADB = FPW >= 16 ? 1 : 16 / FPW;   // 64-coordinate groups loaded per batch
+    static constexpr int LOADB = FPW >= 8 ? 1 : 8 / FPW;   // 64-coordinate groups loaded per batch
     static constexpr int NP = LOG2D <= 4 ? 1 : (LOG2D <= 9 ? 2 : 3);
     static constexpr int radix(int p)
     {
@@ -212,7 +212,7 @@ struct WaveFft {
 constexpr uint32_t kSkipEntry = 3u << 16;
 
 template <int LOG2D, int M>
-__global__ __launch_bounds__(64 * M) void sketch_fft_scan_kernel(
+__global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::LOG2R == 4 ? 3 : 2, 4))) void sketch_fft_scan_kernel(
     const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L, int F,
     float *__restrict__ out, int64_t ld_out)
 {
@@ -277,15 +277,20 @@ __global__ __launch_bounds__(64 * M) void sketch_fft_scan_kernel(
                 for (int s = 0; s < P::FPW; ++s)
                     wave_lds[s * P::PS + sel] = make_float2(old[s].x + val[b][s].x, old[s].y + val[b][s].y);
                 wave_lds_fence();
-                if (lvl == 1) {                       // second coordinate of a bucket inside this group
+                if constexpr (P::LOG2D <= 9) {        // collisions inside a group of 64 are common
+                    if (lvl == 1) {                   // second coordinate of a bucket inside this group
 #pragma unroll
-                    for (int s = 0; s < P::FPW; ++s) old[s] = wave_lds[s * P::PS + off];
+                        for (int s = 0; s < P::FPW; ++s) old[s] = wave_lds[s * P::PS + off];
 #pragma unroll
-                    for (int s = 0; s < P::FPW; ++s)
-                        wave_lds[s * P::PS + off] = make_float2(old[s].x + val[b][s].x, old[s].y + val[b][s].y);
+                        for (int s = 0; s < P::FPW; ++s)
+                            wave_lds[s * P::PS + off] =
+                                make_float2(old[s].x + val[b][s].x, old[s].y + val[b][s].y);
+                    }
+                    wave_lds_fence();
                 }
-                wave_lds_fence();
-                if (lvl == 2) {                       // third or later: rare, LDS float atomics
+                // what is left (third or later in a small transform, any collision in a large
+                // one) is rare: LDS float atomics, about three cycles per active lane
+                if (P::LOG2D <= 9 ? lvl == 2 : (lvl == 1 || lvl == 2)) {
 #pragma unroll
                     for (int s = 0; s < P::FPW; ++s) {
                         atomicAdd(&wave_lds[s * P::PS + off].x, val[b][s].x);

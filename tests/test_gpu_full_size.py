@@ -1,0 +1,102 @@
+"""Parity at the full sizes of the configuration table, in the launch configuration the
+benchmark times (recommended workspace, default stream): sampled rows against the oracle
+(all levels), the hash-independent bucket-sum identity on more rows (a property that holds at
+any size), and the Gram on sampled entries plus full rows."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2501_07145_amd as rfsf
+from paper_2501_07145_amd import workloads as wl
+from tests import pins
+from tests.parity import BF16_BLOCK_TOL, FP32_BLOCK_TOL, GRAM_TOL, block_errors, gram_error
+
+pytestmark = pytest.mark.gpu
+
+
+def _features(w, X, tables, workspace):
+    W, hash_, sign = tables
+    out = rfsf.rfsf_ts_features(torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(),
+                                torch.from_numpy(hash_).cuda(), torch.from_numpy(sign).cuda(),
+                                float(np.float32(w.lengthscale)), w.D, workspace=workspace, rff_bf16=w.rff_bf16)
+    torch.cuda.synchronize()
+    return out
+
+
+def _bucket_sum_identity(w, Xs, tables, got_rows, tol):
+    """sum_j Phi_m[j] = sum_{i_1<...<i_m} prod_k u_k[i_k], u_k[t] = sum_a sign_k[a] delta_k[t][a]."""
+    W, hash_, sign = tables
+    delta = pins.rff_increments_numpy(Xs, W, float(np.float32(w.lengthscale)))
+    u = np.einsum("ntma,ma->ntm", delta, sign.astype(np.float64))
+    e = np.zeros((Xs.shape[0], w.M + 1))
+    e[:, 0] = 1.0
+    for t in range(u.shape[1]):
+        for m in range(w.M, 0, -1):
+            e[:, m] += e[:, m - 1] * u[:, t, m - 1]
+    blocks = got_rows[:, 1:].astype(np.float64).reshape(-1, w.M, w.D)
+    scale = np.abs(blocks).sum(axis=2)                # the sum is compared against the block's 1-norm
+    assert np.all(np.abs(blocks.sum(axis=2) - e[:, 1:]) <= tol * scale)
+
+
+@pytest.mark.parametrize("name,n_oracle,n_identity", [("small", 1000, 0), ("medium", 6, 48), ("long", 3, 8),
+                                                      ("large", 6, 48)])
+def test_full_size(oracle, name, n_oracle, n_identity):
+    w = wl.WORKLOADS[name]
+    tables = wl.make_tables(w, 0)
+    X = wl.make_paths(w, 0)
+    rec, _ = rfsf.rfsf_ts_workspace_bytes(w.N, w.L, w.d, w.M, w.F, w.D, w.rff_bf16)
+    workspace = torch.empty(rec, dtype=torch.uint8, device="cuda")
+    out = _features(w, X, tables, workspace)
+    ls = float(np.float32(w.lengthscale))
+    tol = BF16_BLOCK_TOL if w.rff_bf16 else FP32_BLOCK_TOL
+
+    rng = np.random.default_rng(5)
+    sel = np.unique(np.concatenate([[0, w.N - 1, w.N // 2 - 1, w.N // 2],
+                                    rng.integers(0, w.N, size=max(0, n_oracle - 4))]))[:max(n_oracle, 4)]
+    if n_oracle >= w.N:
+        sel = np.arange(w.N)
+    got = out[torch.from_numpy(sel).cuda()].cpu().numpy()
+    want = oracle.features(X[sel], tables[0], tables[1], tables[2], ls, w.D)
+    err = block_errors(got, want, w.M, w.D)
+    print(f"{name}: {len(sel)} rows, block errors {err}")
+    assert np.all(err <= tol)
+    if w.rff_bf16:      # kernel error alone: oracle on the operands as multiplied
+        hi = wl.round_to_bf16(X[sel])
+        Xm = (hi + wl.round_to_bf16(X[sel] - hi)).astype(np.float32)
+        same = oracle.features(Xm, wl.round_to_bf16(tables[0]), tables[1], tables[2], ls, w.D)
+        err_same = block_errors(got, same, w.M, w.D)
+        print(f"{name}: against same-operand oracle {err_same}")
+        assert np.all(err_same <= FP32_BLOCK_TOL)
+
+    if n_identity and not w.rff_bf16:
+        rows = rng.integers(0, w.N, size=n_identity)
+        _bucket_sum_identity(w, X[rows], tables, out[torch.from_numpy(rows).cuda()].cpu().numpy(), 2e-5)
+
+    # Gram: the second batch for the cross Gram, else the batch with itself
+    if w.N2:
+        X2 = wl.make_paths(w.scaled(N=w.N2), 1)
+        out2 = _features(w.scaled(N=w.N2), X2, tables, workspace)
+    else:
+        out2 = out
+    del workspace
+    K = rfsf.rfsf_ts_gram(out, out2)
+    torch.cuda.synchronize()
+    ii = rng.integers(0, out.shape[0], size=4096)
+    jj = rng.integers(0, out2.shape[0], size=4096)
+    a = out[torch.from_numpy(ii).cuda()].double()
+    b = out2[torch.from_numpy(jj).cuda()].double()
+    ref = (a * b).sum(dim=1).cpu().numpy()            # fp64 dot products of the GPU features
+    gotK = K[torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()].cpu().numpy()
+    kmax = float(K.abs().max())
+    assert np.abs(gotK - ref).max() / kmax <= GRAM_TOL
+    full_rows = np.array([0, out.shape[0] - 1, out.shape[0] // 3])
+    ref_rows = oracle.gram(out[torch.from_numpy(full_rows).cuda()].cpu().numpy(), out2.cpu().numpy()) \
+        if out2.shape[0] * out2.shape[1] <= 60_000_000 else None
+    if ref_rows is not None:
+        assert np.abs(K[torch.from_numpy(full_rows).cuda()].cpu().numpy() - ref_rows).max() / kmax <= GRAM_TOL
+    # end to end on the oracle rows (only when both operands are the sampled batch itself)
+    if not w.N2:
+        Ksub = K[torch.from_numpy(sel).cuda()][:, torch.from_numpy(sel).cuda()].cpu().numpy()
+        assert gram_error(Ksub, oracle.gram(want)) <= (5 * GRAM_TOL if w.rff_bf16 else GRAM_TOL)

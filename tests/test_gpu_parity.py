@@ -91,8 +91,12 @@ def test_chunked_execution_matches(oracle):
     """A workspace that holds only a few sequences forces several launches per call."""
     inp = _random_case(3, 11, 21, 4, 3, 16, 32)
     _, mn = rfsf.rfsf_ts_workspace_bytes(11, 21, 4, 3, 16, 32)
+    _, mn2 = rfsf.rfsf_ts_workspace_bytes(12, 21, 4, 3, 16, 32)
+    rec2, _ = rfsf.rfsf_ts_workspace_bytes(2, 21, 4, 3, 16, 32)
+    per_seq = rec2 - mn2                                 # recommended(N=2) - minimum = one more sequence
+    assert mn == mn2
     for nseq in (1, 3):
-        ws = torch.empty(512 + nseq * (mn - 512), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(mn + (nseq - 1) * per_seq, dtype=torch.uint8, device="cuda")
         _check(inp, 32, oracle, workspace=ws)
     with pytest.raises(binding.RfsfTsError) as e:
         _gpu_features(inp, 32, workspace=torch.empty(mn - 1, dtype=torch.uint8, device="cuda"))
