@@ -8,7 +8,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "librfsf_ts.so")
-SOURCES = ["rfsf_ts_api.hip", "rff_increments.hip", "sketch_fft_scan.hip", "gram.hip"]
+SOURCES = ["rfsf_ts_api.hip", "rff_increments.hip", "sketch_fft_scan.hip", "gram.hip"] + \
+    [f"sketch_fft_scan_d{n}.hip" for n in range(6, 12)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
@@ -26,7 +27,7 @@ def _compile(src: str) -> str:
 
 def build_library(verbose: bool = False) -> str:
     """Compile every HIP source and link the shared library. Always recompiles."""
-    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(os.cpu_count() or 4, 16, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     if verbose:

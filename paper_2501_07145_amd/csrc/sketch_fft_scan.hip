@@ -9,6 +9,7 @@
 // FFT (real parts = step k, imaginary parts = step k+1) and are separated again per bin.
 #include "rfsf_internal.h"
 #include "sketch_fft_scan_tuned.h"
+#include "sketch_fft_scan_dispatch.h"
 
 namespace rfsf {
 namespace {
@@ -136,43 +137,6 @@ __global__ void pack_tables_kernel(const int32_t *hash, const float *sign, int M
     table[i] = (uint32_t)tuned::pad(h) | ((uint32_t)level << 16) | (__float_as_uint(sign[i]) & 0x80000000u);
 }
 
-template <int LOG2D, int M>
-hipError_t launch_tuned(const float *dphi, const uint32_t *table, int64_t n_seq, int64_t L, int F,
-                        float *out, int64_t ld_out, hipStream_t stream)
-{
-    using P = tuned::Plan<LOG2D>;
-    const size_t lds = sizeof(float2) * (size_t)M * P::FPW * P::PS;
-    auto kernel = tuned::sketch_fft_scan_kernel<LOG2D, M>;
-    if (lds > 64 * 1024) {
-        static bool raised = false;
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
-    }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)n_seq), dim3(64 * M), lds, stream, dphi, table, L, F, out, ld_out);
-    return hipGetLastError();
-}
-
-template <int LOG2D>
-hipError_t dispatch_levels(int M, const float *dphi, const uint32_t *table, int64_t n_seq, int64_t L, int F,
-                           float *out, int64_t ld_out, hipStream_t stream)
-{
-    switch (M) {
-        case 1: return launch_tuned<LOG2D, 1>(dphi, table, n_seq, L, F, out, ld_out, stream);
-        case 2: return launch_tuned<LOG2D, 2>(dphi, table, n_seq, L, F, out, ld_out, stream);
-        case 3: return launch_tuned<LOG2D, 3>(dphi, table, n_seq, L, F, out, ld_out, stream);
-        case 4: return launch_tuned<LOG2D, 4>(dphi, table, n_seq, L, F, out, ld_out, stream);
-        case 5: return launch_tuned<LOG2D, 5>(dphi, table, n_seq, L, F, out, ld_out, stream);
-        case 6: return launch_tuned<LOG2D, 6>(dphi, table, n_seq, L, F, out, ld_out, stream);
-        case 7: return launch_tuned<LOG2D, 7>(dphi, table, n_seq, L, F, out, ld_out, stream);
-        case 8: return launch_tuned<LOG2D, 8>(dphi, table, n_seq, L, F, out, ld_out, stream);
-        default: return hipErrorInvalidValue;
-    }
-}
-
 __global__ void fill_trivial_kernel(float *out, int64_t n_seq, int64_t ld_out, int64_t ncols)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -216,12 +180,12 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
     while ((1 << log2D) < D) ++log2D;
     if (sketch_fft_scan_is_tuned(M, D)) {
         switch (log2D) {
-            case 6: return dispatch_levels<6>(M, dphi, table, n_seq, L, F, out, ld_out, stream);
-            case 7: return dispatch_levels<7>(M, dphi, table, n_seq, L, F, out, ld_out, stream);
-            case 8: return dispatch_levels<8>(M, dphi, table, n_seq, L, F, out, ld_out, stream);
-            case 9: return dispatch_levels<9>(M, dphi, table, n_seq, L, F, out, ld_out, stream);
-            case 10: return dispatch_levels<10>(M, dphi, table, n_seq, L, F, out, ld_out, stream);
-            default: return dispatch_levels<11>(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+            case 6: return tuned::dispatch_levels_6(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+            case 7: return tuned::dispatch_levels_7(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+            case 8: return tuned::dispatch_levels_8(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+            case 9: return tuned::dispatch_levels_9(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+            case 10: return tuned::dispatch_levels_10(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+            default: return tuned::dispatch_levels_11(M, dphi, table, n_seq, L, F, out, ld_out, stream);
         }
     }
     const size_t lds = sizeof(float2) * (size_t)(2 * D + D / 2 + 2 * (D / 2 + 1));

@@ -53,13 +53,18 @@ struct Plan {
             case 7: return p == 0 ? 16 : 8;
             case 8: return 16;
             case 9: return p == 0 ? 32 : 16;
-            case 10: return p < 2 ? 16 : 4;
-            default: return p < 2 ? 16 : 8;     // 11
+            // three passes: the small radix goes in the middle, where all of a lane's butterflies
+            // share their twiddles (Ns divides G), which keeps the twiddle registers few
+            case 10: return p == 1 ? 4 : 16;
+            default: return p == 1 ? 8 : 16;    // 11
         }
     }
     static constexpr int Ns(int p) { return p == 0 ? 1 : Ns(p - 1) * radix(p - 1); }
+    // butterflies of pass p with distinct twiddles: butterfly u of a lane has k = (lg + G*u) mod Ns,
+    // the same for every u when Ns divides G
+    static constexpr int tw_sets(int p) { return G % Ns(p) == 0 ? 1 : R / radix(p); }
     // register-array offsets of pass p: twiddles (complex) and write bases
-    static constexpr int tw_off(int p) { return p <= 1 ? 0 : tw_off(p - 1) + (R / radix(p - 1)) * (radix(p - 1) - 1); }
+    static constexpr int tw_off(int p) { return p <= 1 ? 0 : tw_off(p - 1) + tw_sets(p - 1) * (radix(p - 1) - 1); }
     static constexpr int wb_off(int p) { return p == 0 ? 0 : wb_off(p - 1) + R / radix(p - 1); }
     static constexpr int NTW = NP == 1 ? 1 : tw_off(NP);
     static constexpr int NWB = wb_off(NP);
@@ -153,7 +158,12 @@ struct WaveFft {
                 const int j = lg + P::G * u;
                 const int k = j & (Ns - 1);
                 wbase[P::wb_off(PI) + u] = pad((j - k) * r + k);
-                if constexpr (PI > 0) {
+            }
+            if constexpr (PI > 0) {
+                constexpr int NSETS = P::tw_sets(PI);
+#pragma unroll
+                for (int u = 0; u < NSETS; ++u) {
+                    const int k = (lg + P::G * u) & (Ns - 1);
 #pragma unroll
                     for (int t = 1; t < r; ++t) {
                         float s, c;
@@ -188,7 +198,7 @@ struct WaveFft {
                 for (int t = 0; t < r; ++t) {
                     x[t] = v[u + t * NB];
                     if constexpr (PI > 0) {
-                        if (t > 0) x[t] = cmulf(x[t], tw[P::tw_off(PI) + u * (r - 1) + (t - 1)]);
+                        if (t > 0) x[t] = cmulf(x[t], tw[P::tw_off(PI) + (P::tw_sets(PI) == 1 ? 0 : u) * (r - 1) + (t - 1)]);
                     }
                 }
                 dft_dif<r, 0, r>(x);
@@ -212,7 +222,7 @@ struct WaveFft {
 constexpr uint32_t kSkipEntry = 3u << 16;
 
 template <int LOG2D, int M>
-__global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::LOG2R == 4 ? 3 : 2, 4))) void sketch_fft_scan_kernel(
+__global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::LOG2R == 4 ? 4 : 2, 4))) void sketch_fft_scan_kernel(
     const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L, int F,
     float *__restrict__ out, int64_t ld_out)
 {
