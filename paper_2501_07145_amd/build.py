@@ -19,9 +19,12 @@ FLAGS = [
 ]
 
 
+EXTRA = os.environ.get("RFSF_EXTRA_HIPCC_FLAGS", "").split()   # for experiments, e.g. -DRFSF_PREFETCH=1
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-    subprocess.run([HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
+    subprocess.run([HIPCC, *FLAGS, *EXTRA, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
     return obj
 
 

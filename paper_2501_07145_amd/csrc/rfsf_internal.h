@@ -25,13 +25,15 @@ hipError_t launch_rff_increments(const float *X, const float *W, float inv_lengt
 // Steps 3-4: CountSketch, FFT-domain level recursion over time, inverse transform; writes
 // columns 0 .. M*D of `n_seq` rows of out (already offset to the chunk).
 // `state` is scratch for the generic kernel: n_seq * M * (D/2+1) complex floats.
-// `table` (M * 2F uint32, filled by launch_pack_tables once per call) feeds the tuned kernel.
+// `table` (sketch_fft_scan_table_bytes, filled by launch_pack_tables once per call) feeds the tuned kernel.
 hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
                                   const uint32_t *table, int64_t n_seq, int64_t L, int M, int F, int D,
                                   float *out, int64_t ld_out, float *state, hipStream_t stream);
 hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int F, int D, uint32_t *table,
                               hipStream_t stream);
-bool sketch_fft_scan_is_tuned(int M, int D);
+bool sketch_fft_scan_is_tuned(int M, int F, int D);
+size_t sketch_fft_scan_table_bytes(int M, int F, int D);   // 0 when the generic kernel runs
+size_t sketch_fft_scan_lds_bytes(int M, int F, int D);
 size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D);
 
 // Level-0 column and zero blocks for sequences without increments (L == 1).

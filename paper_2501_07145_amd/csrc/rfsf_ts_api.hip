@@ -32,6 +32,7 @@ namespace {
 
 constexpr size_t kAlign = 256;
 constexpr size_t kChunkBytesTarget = (size_t)32 << 30;   // increments held per launch, at most
+constexpr size_t kIncrementTail = 4096;   // the sketch kernel may read up to 1023 floats past the last row
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -59,7 +60,7 @@ void per_sequence_bytes(const rfsf_ts_shape *s, size_t *incr, size_t *state)
 // Fixed part: packed hash/sign table plus room for aligning the three sections.
 size_t fixed_bytes(const rfsf_ts_shape *s)
 {
-    return align_up((size_t)s->M * 2u * (size_t)s->F * sizeof(uint32_t)) + 3 * kAlign;
+    return align_up(rfsf::sketch_fft_scan_table_bytes(s->M, s->F, s->D)) + kIncrementTail + 3 * kAlign;
 }
 
 int64_t chunk_for(const rfsf_ts_shape *s, size_t bytes)
@@ -139,8 +140,8 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
     char *base = static_cast<char *>(workspace);
     const size_t mis = (size_t)(reinterpret_cast<uintptr_t>(base) % kAlign);
     char *p_table = base + (mis ? kAlign - mis : 0);
-    char *p_incr = p_table + align_up((size_t)shape->M * 2u * (size_t)shape->F * sizeof(uint32_t));
-    char *p_state = p_incr + align_up((size_t)chunk * incr);
+    char *p_incr = p_table + align_up(rfsf::sketch_fft_scan_table_bytes(shape->M, shape->F, shape->D));
+    char *p_state = p_incr + align_up((size_t)chunk * incr + kIncrementTail);
     float *dphi = reinterpret_cast<float *>(p_incr);
     float *state = reinterpret_cast<float *>(p_state);
     uint32_t *table = reinterpret_cast<uint32_t *>(p_table);

@@ -121,20 +121,70 @@ __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
     }
 }
 
-// hash/sign of every (level, coordinate) packed for the tuned kernel (layout: see kSkipEntry).
-// The collision level counts the earlier coordinates of the same aligned group of 64 (within
-// the level's own 2F coordinates) that fall into the same bucket.
-__global__ void pack_tables_kernel(const int32_t *hash, const float *sign, int M, int twoF, int D, uint32_t *table)
+// Builds the per-level tables of the tuned kernel (layout: tuned::TableLayout). One workgroup per
+// level. rank(a) = number of earlier coordinates of the level in the same bucket; ranks 0 and 1
+// go to the gather words, ranks >= 2 become fold entries, ordered by rank and padded so that a
+// round of G entries never mixes two ranks (hence never repeats a bucket).
+__global__ __launch_bounds__(256) void build_tables_kernel(
+    const int32_t *__restrict__ hash, const float *__restrict__ sign, int twoF, int D, int G, int LOADB,
+    int PD, uint32_t *__restrict__ table)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= (int64_t)M * twoF) return;
-    const int a = (int)(i % twoF);
-    const int64_t base = i - a;
-    const int h = hash[i] & (D - 1);
-    int level = 0;
-    for (int a2 = a & ~63; a2 < a; ++a2) level += (hash[base + a2] & (D - 1)) == h;
-    if (level > 2) level = 2;
-    table[i] = (uint32_t)tuned::pad(h) | ((uint32_t)level << 16) | (__float_as_uint(sign[i]) & 0x80000000u);
+    extern __shared__ int table_scratch[];
+    int *h = table_scratch, *rk = h + twoF, *cls = rk + twoF, *src0 = cls + twoF + 1, *src1 = src0 + D;
+    __shared__ int max_rank, n_rounds;
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const tuned::TableLayout tl = tuned::table_layout(D, G, LOADB, twoF);
+    uint32_t *tab = table + (int64_t)m * tl.words;
+    const uint32_t zero_off = (uint32_t)tuned::zero_slot(PD, twoF) * 8u;
+
+    for (int a = tid; a < twoF; a += 256) h[a] = hash[(int64_t)m * twoF + a] & (D - 1);
+    for (int e = tid; e < D; e += 256) { src0[e] = -1; src1[e] = -1; }
+    for (int r = tid; r <= twoF; r += 256) cls[r] = 0;
+    if (tid == 0) max_rank = 0;
+    __syncthreads();
+    for (int a = tid; a < twoF; a += 256) {
+        int r = 0;
+        for (int a2 = 0; a2 < a; ++a2) r += h[a2] == h[a];
+        rk[a] = r;
+        if (r == 0) src0[h[a]] = a;
+        else if (r == 1) src1[h[a]] = a;
+        else { atomicAdd(&cls[r], 1); atomicMax(&max_rank, r); }
+    }
+    __syncthreads();
+    if (tid == 0) {                       // class sizes -> start offsets, each class padded to G
+        int off = 0;
+        for (int r = 2; r <= max_rank; ++r) {
+            const int c = cls[r];
+            cls[r] = off;
+            off += (c + G - 1) / G * G;
+        }
+        n_rounds = off / G;
+        tab[0] = (uint32_t)n_rounds;
+    }
+    __syncthreads();
+    for (int i = tid; i < n_rounds * G; i += 256) tab[tl.fold + i] = zero_off | (tuned::kFoldPad << 16);
+    for (int e = tid; e < D; e += 256) {
+        const uint32_t s0 = src0[e] >= 0 ? (uint32_t)src0[e] * 8u : zero_off;
+        const uint32_t s1 = src1[e] >= 0 ? (uint32_t)src1[e] * 8u : zero_off;
+        tab[tl.gather + e] = s0 | (s1 << 16);
+    }
+    for (int i = tid; i < tl.nbatch * 64; i += 256) {
+        const int bi = i >> 6, lane = i & 63;
+        uint32_t w = 0;
+        for (int b = 0; b < LOADB; ++b) {
+            const int a = bi * 64 * LOADB + 64 * b + lane;
+            if (a < twoF && (__float_as_uint(sign[(int64_t)m * twoF + a]) >> 31)) w |= 1u << b;
+        }
+        tab[tl.signs + i] = w;
+    }
+    __syncthreads();                      // padding entries are in place before the real ones land
+    for (int a = tid; a < twoF; a += 256) {
+        const int r = rk[a];
+        if (r < 2) continue;
+        int idx = 0;
+        for (int a2 = 0; a2 < a; ++a2) idx += rk[a2] == r;
+        tab[tl.fold + cls[r] + idx] = ((uint32_t)a * 8u) | (((uint32_t)src0[h[a]] * 8u) << 16);
+    }
 }
 
 __global__ void fill_trivial_kernel(float *out, int64_t n_seq, int64_t ld_out, int64_t ncols)
@@ -160,14 +210,59 @@ size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D)
     return (size_t)n_seq * (size_t)M * (size_t)(D / 2 + 1) * sizeof(float2);
 }
 
-bool sketch_fft_scan_is_tuned(int M, int D) { return M <= 8 && D >= 64 && D <= 2048; }
+namespace {
+struct TunedGeometry { int G, LOADB, PD, FPW, NTWL; };
+bool tuned_geometry(int D, TunedGeometry *g)
+{
+    switch (D) {
+#define RFSF_GEOM(L2) case 1 << L2: *g = {tuned::Plan<L2>::G, tuned::Plan<L2>::LOADB, tuned::Plan<L2>::PD, tuned::Plan<L2>::FPW, tuned::Plan<L2>::NTWL}; return true;
+        RFSF_GEOM(6) RFSF_GEOM(7) RFSF_GEOM(8) RFSF_GEOM(9) RFSF_GEOM(10) RFSF_GEOM(11)
+#undef RFSF_GEOM
+        default: return false;
+    }
+}
+constexpr size_t kLdsPerCu = 160 * 1024;
+}  // namespace
+
+size_t sketch_fft_scan_lds_bytes(int M, int F, int D)
+{
+    TunedGeometry g;
+    if (!tuned_geometry(D, &g)) return 0;
+    return sizeof(float2) * ((size_t)M * g.FPW * tuned::slot_stride(g.PD, 2 * F) + g.NTWL);
+}
+
+bool sketch_fft_scan_is_tuned(int M, int F, int D)
+{
+    TunedGeometry g;
+    if (M > 8 || F > 4095 || !tuned_geometry(D, &g)) return false;
+    return sketch_fft_scan_lds_bytes(M, F, D) <= kLdsPerCu;
+}
+
+size_t sketch_fft_scan_table_bytes(int M, int F, int D)
+{
+    TunedGeometry g;
+    if (!sketch_fft_scan_is_tuned(M, F, D) || !tuned_geometry(D, &g)) return 0;
+    return sizeof(uint32_t) * (size_t)M * tuned::table_layout(D, g.G, g.LOADB, 2 * F).words;
+}
 
 hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int F, int D, uint32_t *table,
                               hipStream_t stream)
 {
-    const int64_t count = (int64_t)M * 2 * F;
-    hipLaunchKernelGGL(pack_tables_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream,
-                       hash, sign, M, 2 * F, D, table);
+    TunedGeometry g;
+    if (!sketch_fft_scan_is_tuned(M, F, D) || !tuned_geometry(D, &g)) return hipSuccess;   // generic kernel: no table
+    const int twoF = 2 * F;
+    const size_t lds = sizeof(int) * (size_t)(3 * twoF + 1 + 2 * D);
+    if (lds > 64 * 1024) {
+        static size_t granted = 0;
+        if (lds > granted) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(build_tables_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            granted = lds;
+        }
+    }
+    hipLaunchKernelGGL(build_tables_kernel, dim3((unsigned)M), dim3(256), lds, stream, hash, sign, twoF, D, g.G,
+                       g.LOADB, g.PD, table);
     return hipGetLastError();
 }
 
@@ -178,7 +273,7 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
     if (n_seq == 0) return hipSuccess;
     int log2D = 0;
     while ((1 << log2D) < D) ++log2D;
-    if (sketch_fft_scan_is_tuned(M, D)) {
+    if (sketch_fft_scan_is_tuned(M, F, D)) {
         switch (log2D) {
             case 6: return tuned::dispatch_levels_6(M, dphi, table, n_seq, L, F, out, ld_out, stream);
             case 7: return tuned::dispatch_levels_7(M, dphi, table, n_seq, L, F, out, ld_out, stream);

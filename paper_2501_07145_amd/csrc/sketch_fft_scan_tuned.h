@@ -3,21 +3,25 @@
 //
 // Work decomposition (one workgroup per sequence, M wavefronts, wavefront m owns level m):
 //   per iteration every wavefront handles FPW pairs of consecutive time steps of its level:
-//     1. clears its LDS slots and scatter-adds the signed increments of the 2*FPW time steps
-//        into them (step 2k goes to the real parts, step 2k+1 to the imaginary parts of slot
-//        k). LDS float atomics cost about three cycles per lane on this chip, so conflicts are
-//        handled wavefront-locally instead: the 2F coordinates are taken 64 at a time; a
-//        precomputed level says how many earlier coordinates of the same 64 share the bucket.
-//        Level-0 lanes hit distinct buckets and do a plain read-add-write; for D <= 512 the
-//        level-1 lanes do the same in a second masked round; the rare rest uses ds_add_f32.
-//        Successive groups of 64 are ordered by the in-order LDS queue of the wavefront,
-//     2. runs FPW complex FFTs of length D held in its own LDS slots, G = D/R lanes per
+//     1. CountSketch as a gather. The signed increments of the 2*FPW time steps are written to
+//        LDS in their natural order (step 2k -> real part, step 2k+1 -> imaginary part of the
+//        float2 of coordinate a, one staging area per pair). A table built once per call lists,
+//        for every bucket, the first two coordinates that hash to it; the few coordinates that
+//        are third or later in their bucket are first folded into the bucket's first coordinate
+//        by conflict-free read-add-write rounds (one round per rank, so no two lanes of a round
+//        touch the same float2). Then each FFT lane reads the (at most two) sources of each of
+//        its R buckets straight into its FFT registers. No LDS atomics (a full-wavefront
+//        ds_add_f32 costs ~190 cycles on this chip), no clearing, and the summation order is
+//        fixed, so results are bit-reproducible.
+//     2. FPW complex FFTs of length D held in the wavefront's LDS slots, G = D/R lanes per
 //        transform with R points per lane in registers (Stockham passes, radix up to 32 in
 //        registers, one LDS exchange per pass, no workgroup barrier inside the transform),
 //   then, after one barrier, every thread owns a few frequency bins, separates the two real
 //   transforms of each slot, and advances the accumulators A_1..A_M of its bins by the two
 //   time steps (A_m += A_{m-1}(before the step) * C_m, A_0 = 1).
-//   After the last time step, wavefront m transforms A_m back and writes block m of the row.
+//   The rows of the next iteration are fetched into registers while the barrier and the
+//   recurrence run. After the last time step, wavefront m transforms A_m back and writes
+//   block m of the row.
 //
 // The increments arrive pre-multiplied by 1/2 (done by the producing kernel), which is the
 // factor of the two-for-one separation  C0 = (Z[f] + conj Z[D-f]) / 2,  C1 = (Z[f] - conj Z[D-f]) / 2i.
@@ -41,8 +45,7 @@ struct Plan {
     static constexpr int G = D / R;             // lanes per transform
     static constexpr int FPW = 64 / G;          // transforms per wavefront
     static constexpr int PD = D + D / 16;       // padded transform length in float2
-    static constexpr int PS = PD + 64;          // slot stride: one spare float2 per lane behind the data
-    static constexpr int LOADB = FPW >= 8 ? 1 : 8 / FPW;   // 64-coordinate groups loaded per batch
+    static constexpr int LOADB = FPW >= 16 ? 1 : 16 / FPW;   // 64-coordinate groups fetched per batch
     static constexpr int NP = LOG2D <= 4 ? 1 : (LOG2D <= 9 ? 2 : 3);
     static constexpr int radix(int p)
     {
@@ -63,13 +66,57 @@ struct Plan {
     // butterflies of pass p with distinct twiddles: butterfly u of a lane has k = (lg + G*u) mod Ns,
     // the same for every u when Ns divides G
     static constexpr int tw_sets(int p) { return G % Ns(p) == 0 ? 1 : R / radix(p); }
-    // register-array offsets of pass p: twiddles (complex) and write bases
-    static constexpr int tw_off(int p) { return p <= 1 ? 0 : tw_off(p - 1) + tw_sets(p - 1) * (radix(p - 1) - 1); }
+    // The twiddles of a radix-16 pass (15 per set) would cost 30 registers per set; they live in an
+    // LDS table shared by the workgroup instead. Smaller passes keep theirs in registers.
+    static constexpr bool tw_in_lds(int p) { return p > 0 && radix(p) >= 16; }
+    static constexpr int tw_regs(int p) { return (p == 0 || tw_in_lds(p)) ? 0 : tw_sets(p) * (radix(p) - 1); }
+    static constexpr int tw_lds(int p) { return tw_in_lds(p) ? tw_sets(p) * (radix(p) - 1) * G : 0; }   // float2 entries
+    // array offsets of pass p: register twiddles (complex), LDS twiddles (float2) and write bases
+    static constexpr int tw_off(int p) { return p <= 1 ? 0 : tw_off(p - 1) + tw_regs(p - 1); }
+    static constexpr int twl_off(int p) { return p <= 1 ? 0 : twl_off(p - 1) + tw_lds(p - 1); }
+    static constexpr int NTWL = twl_off(NP);
     static constexpr int wb_off(int p) { return p == 0 ? 0 : wb_off(p - 1) + R / radix(p - 1); }
-    static constexpr int NTW = NP == 1 ? 1 : tw_off(NP);
+    static constexpr int NTW = tw_off(NP) == 0 ? 1 : tw_off(NP);
     static constexpr int NWB = wb_off(NP);
     static constexpr int roff(int q) { return G >= 16 ? q * (G + G / 16) : pad(G * q); }
 };
+
+// Geometry of one LDS slot (float2 units): [0, ZS) data -- the staging area uses [0, 2F), the
+// transform [0, PD) --, [ZS] a float2 that is always zero (source of buckets without a first or
+// second coordinate).
+__host__ __device__ constexpr int zero_slot(int PD, int twoF) { return PD > twoF ? PD : twoF; }
+__host__ __device__ constexpr int slot_stride(int PD, int twoF) { return (zero_slot(PD, twoF) + 2) & ~1; }
+
+// Per-level table built once per call (uint32 words):
+//   [0]                 NG, number of fold rounds
+//   [64, 64 + D)        gather words: low 16 bits byte offset of the bucket's first coordinate in the
+//                       staging area, high 16 bits of its second one (zero float2 if there is none)
+//   [.., + NBATCH*64)   sign words: bit b of word (batch, lane) is the sign of coordinate
+//                       batch*64*LOADB + 64*b + lane
+//   [.., + 2F*G)        fold entries, G per round: low 16 bits byte offset of the coordinate to fold,
+//                       high 16 bits byte offset of the first coordinate of its bucket (0xffff: padding)
+struct TableLayout {
+    int nbatch, gather, signs, fold, words;
+};
+__host__ __device__ inline TableLayout table_layout(int D, int G, int LOADB, int twoF)
+{
+    TableLayout t;
+    t.nbatch = (twoF + 64 * LOADB - 1) / (64 * LOADB);
+    t.gather = 64;
+    t.signs = t.gather + D;
+    t.fold = t.signs + t.nbatch * 64;
+    t.words = (t.fold + twoF * G + 63) & ~63;
+    return t;
+}
+constexpr uint32_t kFoldPad = 0xffffu;
+constexpr int kFoldInRegs = 8;
+#ifndef RFSF_WAVES_R16
+#define RFSF_WAVES_R16 4
+#endif
+#ifndef RFSF_PREFETCH
+#define RFSF_PREFETCH 0
+#endif
+constexpr bool kPrefetch = RFSF_PREFETCH != 0;   // fetch the next iteration's rows before the barrier      // fold rounds whose entries are fetched with the other tables
 
 // cos(k pi / 16), k = 0..8
 __device__ constexpr float kCos16[9] = {1.0f, 0.98078528040323043f, 0.92387953251128674f, 0.83146961230254524f,
@@ -141,11 +188,33 @@ struct WaveFft {
     float2 tw[P::NTW];
     int wbase[P::NWB];
     int rbase;
+    const float2 *twl;      // LDS twiddle table of the radix-16 passes, entry ((set*(r-1) + t-1)*G + lg)
 
-    __device__ __forceinline__ void init(int lg)
+    __device__ __forceinline__ void init(int lg, float2 *twl_table)
     {
         rbase = pad(lg);
+        twl = twl_table + lg;
         init_pass<0>(lg);
+        fill_table<1>(twl_table);
+    }
+
+    // Workgroup-cooperative fill of the LDS twiddle table; the caller synchronises afterwards.
+    template <int PI>
+    __device__ __forceinline__ void fill_table(float2 *twl_table)
+    {
+        if constexpr (PI < P::NP) {
+            if constexpr (P::tw_in_lds(PI)) {
+                constexpr int r = P::radix(PI), Ns = P::Ns(PI);
+                for (int i = threadIdx.x; i < P::tw_lds(PI); i += blockDim.x) {
+                    const int l = i % P::G, ut = i / P::G, t = ut % (r - 1) + 1, u = ut / (r - 1);
+                    const int k = (l + P::G * u) & (Ns - 1);
+                    float s, c;
+                    sincospif(-2.0f * (float)(k * t) / (float)(Ns * r), &s, &c);
+                    twl_table[P::twl_off(PI) + i] = make_float2(c, s);
+                }
+            }
+            fill_table<PI + 1>(twl_table);
+        }
     }
 
     template <int PI>
@@ -159,7 +228,7 @@ struct WaveFft {
                 const int k = j & (Ns - 1);
                 wbase[P::wb_off(PI) + u] = pad((j - k) * r + k);
             }
-            if constexpr (PI > 0) {
+            if constexpr (PI > 0 && !P::tw_in_lds(PI)) {
                 constexpr int NSETS = P::tw_sets(PI);
 #pragma unroll
                 for (int u = 0; u < NSETS; ++u) {
@@ -184,6 +253,11 @@ struct WaveFft {
         for (int q = 0; q < P::R; ++q) v[q] = slot[rbase + P::roff(q)];
         run_pass<0>(slot, v);
     }
+    // The same with the input already in registers: v[q] is point lg + G*q of the lane's transform.
+    __device__ __forceinline__ void run_from_registers(float2 *slot, float2 (&v)[P::R]) const
+    {
+        run_pass<0>(slot, v);
+    }
 
     template <int PI>
     __device__ __forceinline__ void run_pass(float2 *slot, float2 (&v)[P::R]) const
@@ -198,7 +272,15 @@ struct WaveFft {
                 for (int t = 0; t < r; ++t) {
                     x[t] = v[u + t * NB];
                     if constexpr (PI > 0) {
-                        if (t > 0) x[t] = cmulf(x[t], tw[P::tw_off(PI) + (P::tw_sets(PI) == 1 ? 0 : u) * (r - 1) + (t - 1)]);
+                        constexpr int set = P::tw_sets(PI) == 1 ? 0 : 1;    // multiplier of u below
+                        if (t > 0) {
+                            if constexpr (P::tw_in_lds(PI)) {
+                                x[t] = cmulf(x[t], twl[P::twl_off(PI) + ((set * u) * (r - 1) + (t - 1)) * P::G]);
+                                if (t % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // bound the twiddles in flight
+                            } else {
+                                x[t] = cmulf(x[t], tw[P::tw_off(PI) + (set * u) * (r - 1) + (t - 1)]);
+                            }
+                        }
                     }
                 }
                 dft_dif<r, 0, r>(x);
@@ -216,31 +298,33 @@ struct WaveFft {
     }
 };
 
-// Packed table entry: bits 0-15 float2 index of the bucket inside a padded slot, bits 16-17
-// collision level inside the group of 64 coordinates (0, 1, 2 = two or more earlier ones,
-// 3 = no coordinate), bit 31 the sign.
-constexpr uint32_t kSkipEntry = 3u << 16;
-
 template <int LOG2D, int M>
-__global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::LOG2R == 4 ? 4 : 2, 4))) void sketch_fft_scan_kernel(
+__global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::LOG2R == 4 ? RFSF_WAVES_R16 : 2, 4))) void sketch_fft_scan_kernel(
     const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L, int F,
     float *__restrict__ out, int64_t ld_out)
 {
     using P = Plan<LOG2D>;
     constexpr int D = P::D, NT = 64 * M, NB = D / 2 + 1, BPT = (NB + NT - 1) / NT;
-    extern __shared__ float2 lds[];                    // [M][FPW][PS]
-    const int tid = threadIdx.x, lane = tid & 63, m = tid >> 6;
+    extern __shared__ float2 lds[];                    // [M][FPW][PS] slots, then the twiddle table
+    const int tid = threadIdx.x, lane = tid & 63, m = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int slot_id = lane / P::G, lg = lane % P::G;
-    float2 *wave_lds = lds + (size_t)m * P::FPW * P::PS;
-    float2 *my_slot = wave_lds + slot_id * P::PS;
-    const int64_t n = blockIdx.x, T = L - 1;
     const int twoF = 2 * F;
+    const int ZS = zero_slot(P::PD, twoF), PS = slot_stride(P::PD, twoF);
+    float2 *twl_table = lds + (size_t)M * P::FPW * PS;          // behind the slots
+    float2 *wave_lds = lds + (size_t)m * P::FPW * PS;
+    float2 *my_slot = wave_lds + slot_id * PS;
+    char *my_slot_bytes = reinterpret_cast<char *>(my_slot);
+    const int64_t n = blockIdx.x, T = L - 1;
     const int64_t rf = (int64_t)M * twoF;
     const float *seq = dphi + n * L * rf + (int64_t)m * twoF;   // row k of this level: seq + k * rf
-    const uint32_t *tab = table + (int64_t)m * twoF;
+    const TableLayout tl = table_layout(D, P::G, P::LOADB, twoF);
+    const uint32_t *tab = table + (int64_t)m * tl.words;
+    const int NG = (int)tab[0];
 
     WaveFft<P> fft;
-    fft.init(lg);
+    fft.init(lg, twl_table);
+    if (lg == 0) my_slot[ZS] = make_float2(0.f, 0.f);
+    __syncthreads();
 
     float2 A[BPT][M];
 #pragma unroll
@@ -248,71 +332,90 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
 #pragma unroll
         for (int l = 0; l < M; ++l) A[b][l] = make_float2(0.f, 0.f);
 
-    const int64_t pairs = (T + 1) / 2;
-    for (int64_t pair0 = 0; pair0 < pairs; pair0 += P::FPW) {
-        // 1. clear this wavefront's slots, then signed scatter-add of 2*FPW time steps
-        for (int i = lane; i < P::FPW * P::PS; i += 64) wave_lds[i] = make_float2(0.f, 0.f);
-        wave_lds_fence();
-        for (int a0 = 0; a0 < twoF; a0 += 64 * P::LOADB) {
-            uint32_t tb[P::LOADB];
-            float2 val[P::LOADB][P::FPW];
-            // all global loads of the batch are issued before the first use
+    // Rows 2*(pair0+s) and 2*(pair0+s)+1 of this level, coordinates a0 + 64*b + lane, as (re, im).
+    // Row addresses are wavefront-uniform (scalar base) and the coordinate offset is lane + constant,
+    // so a load is one instruction with an immediate offset. Rows beyond the last increment are
+    // redirected to the last one and zeroed; coordinates beyond 2F read the following floats of the
+    // workspace (which is padded at its end for this) and are dropped when staging.
+    float2 val[P::LOADB][P::FPW];
+    auto fetch = [&](int64_t pair0, int a0) {
+#pragma unroll
+        for (int s = 0; s < P::FPW; ++s) {
+            const int64_t k0 = 2 * (pair0 + s);
+            const int64_t kk0 = k0 < T ? k0 : T - 1, kk1 = k0 + 1 < T ? k0 + 1 : T - 1;
+            const float *r0 = seq + kk0 * rf + a0, *r1 = seq + kk1 * rf + a0;
+            const float z0 = k0 < T ? 1.f : 0.f, z1 = k0 + 1 < T ? 1.f : 0.f;
+#pragma unroll
+            for (int b = 0; b < P::LOADB; ++b) val[b][s] = make_float2(r0[lane + 64 * b] * z0, r1[lane + 64 * b] * z1);
+        }
+    };
+    // Signs applied, values written to the staging areas (natural coordinate order).
+    auto stage = [&](int a0, uint32_t sign_word) {
+#pragma unroll
+        for (int s = 0; s < P::FPW; ++s) {
+            float2 *dst = wave_lds + s * PS + a0 + lane;
 #pragma unroll
             for (int b = 0; b < P::LOADB; ++b) {
-                const int a = a0 + 64 * b + lane;
-                const bool ok = a < twoF;
-                const int aa = ok ? a : twoF - 1;
-                const uint32_t t = tab[aa];
-                tb[b] = ok ? t : kSkipEntry;
-                const uint32_t sgn = t & 0x80000000u;
-#pragma unroll
-                for (int s = 0; s < P::FPW; ++s) {
-                    const int64_t k0 = 2 * (pair0 + s);
-                    const int64_t kk0 = k0 < T ? k0 : T - 1, kk1 = k0 + 1 < T ? k0 + 1 : T - 1;
-                    const float x0 = __uint_as_float(__float_as_uint(seq[kk0 * rf + aa]) ^ sgn);
-                    const float x1 = __uint_as_float(__float_as_uint(seq[kk1 * rf + aa]) ^ sgn);
-                    val[b][s] = make_float2(k0 < T ? x0 : 0.f, k0 + 1 < T ? x1 : 0.f);
-                }
-            }
-#pragma unroll
-            for (int b = 0; b < P::LOADB; ++b) {
-                const uint32_t lvl = (tb[b] >> 16) & 3u;
-                const int off = (int)(tb[b] & 0xffffu);
-                // round 0: every lane issues; lanes of other levels use their spare float2
-                const int sel = lvl == 0 ? off : P::PD + lane;
-                float2 old[P::FPW];
-#pragma unroll
-                for (int s = 0; s < P::FPW; ++s) old[s] = wave_lds[s * P::PS + sel];
-#pragma unroll
-                for (int s = 0; s < P::FPW; ++s)
-                    wave_lds[s * P::PS + sel] = make_float2(old[s].x + val[b][s].x, old[s].y + val[b][s].y);
-                wave_lds_fence();
-                if constexpr (P::LOG2D <= 9) {        // collisions inside a group of 64 are common
-                    if (lvl == 1) {                   // second coordinate of a bucket inside this group
-#pragma unroll
-                        for (int s = 0; s < P::FPW; ++s) old[s] = wave_lds[s * P::PS + off];
-#pragma unroll
-                        for (int s = 0; s < P::FPW; ++s)
-                            wave_lds[s * P::PS + off] =
-                                make_float2(old[s].x + val[b][s].x, old[s].y + val[b][s].y);
-                    }
-                    wave_lds_fence();
-                }
-                // what is left (third or later in a small transform, any collision in a large
-                // one) is rare: LDS float atomics, about three cycles per active lane
-                if (P::LOG2D <= 9 ? lvl == 2 : (lvl == 1 || lvl == 2)) {
-#pragma unroll
-                    for (int s = 0; s < P::FPW; ++s) {
-                        atomicAdd(&wave_lds[s * P::PS + off].x, val[b][s].x);
-                        atomicAdd(&wave_lds[s * P::PS + off].y, val[b][s].y);
-                    }
-                }
-                wave_lds_fence();
+                const uint32_t sgn = (sign_word << (31 - b)) & 0x80000000u;
+                if (a0 + 64 * b + lane < twoF)
+                    dst[64 * b] = make_float2(__uint_as_float(__float_as_uint(val[b][s].x) ^ sgn),
+                                              __uint_as_float(__float_as_uint(val[b][s].y) ^ sgn));
             }
         }
-        // 2. FPW transforms per wavefront (run() starts with the intra-wavefront fence)
+    };
+
+    const int64_t pairs = (T + 1) / 2;
+    if (kPrefetch) fetch(0, 0);
+    for (int64_t pair0 = 0; pair0 < pairs; pair0 += P::FPW) {
+        // Tables of this level. They are the same every iteration and stay in L1/L2; the pointer is
+        // laundered so that the compiler reloads them here instead of keeping ~90 loop-invariant
+        // registers (table words and everything derived from them) alive across the transform.
+        const uint32_t *tabi = tab;
+        asm volatile("" : "+s"(tabi));
+        uint32_t gw[P::R], fw[kFoldInRegs];
+#pragma unroll
+        for (int q = 0; q < P::R; ++q) gw[q] = tabi[tl.gather + lg + P::G * q];
+#pragma unroll
+        for (int g = 0; g < kFoldInRegs; ++g) fw[g] = g < NG ? tabi[tl.fold + g * P::G + lg] : kFoldPad << 16;
+        const uint32_t sw0 = tabi[tl.signs + lane];
+
+        // 1a. staging: the prefetched first batch, then any further batches
+        if (!kPrefetch) fetch(pair0, 0);
+        stage(0, sw0);
+        for (int bi = 1; bi < tl.nbatch; ++bi) {
+            const int a0 = bi * 64 * P::LOADB;
+            fetch(pair0, a0);
+            stage(a0, tabi[tl.signs + bi * 64 + lane]);
+        }
         wave_lds_fence();
-        fft.run(my_slot);
+        // 1b. fold the third and later coordinates of a bucket into its first one, one rank per round
+        auto fold = [&](uint32_t w) {
+            const uint32_t own = w & 0xffffu, tgt = w >> 16;
+            if (tgt != kFoldPad) {
+                const float2 x = *reinterpret_cast<const float2 *>(my_slot_bytes + own);
+                const float2 y = *reinterpret_cast<const float2 *>(my_slot_bytes + tgt);
+                *reinterpret_cast<float2 *>(my_slot_bytes + tgt) = make_float2(x.x + y.x, x.y + y.y);
+            }
+            wave_lds_fence();
+        };
+#pragma unroll
+        for (int g = 0; g < kFoldInRegs; ++g)
+            if (g < NG) fold(fw[g]);
+        for (int g = kFoldInRegs; g < NG; ++g) fold(tabi[tl.fold + g * P::G + lg]);
+        // 1c. gather: first and second coordinate of each of this lane's buckets
+        float2 v[P::R];
+#pragma unroll
+        for (int q = 0; q < P::R; ++q) {
+            const float2 x0 = *reinterpret_cast<const float2 *>(my_slot_bytes + (gw[q] & 0xffffu));
+            const float2 x1 = *reinterpret_cast<const float2 *>(my_slot_bytes + (gw[q] >> 16));
+            v[q] = make_float2(x0.x + x1.x, x0.y + x1.y);
+            // keep the scheduler from issuing all 2R reads at once (it would need 4R registers)
+            if (q % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+        // 2. FPW transforms per wavefront, in place in the slots
+        fft.run_from_registers(my_slot, v);
+        // rows of the next iteration: in flight during the barrier and the recurrence
+        if (kPrefetch && pair0 + P::FPW < pairs) fetch(pair0 + P::FPW, 0);
         __syncthreads();
         // 3. per-bin separation and recurrence, two time steps per slot, levels ascending
 #pragma unroll
@@ -325,7 +428,7 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
                     float2 p0 = make_float2(1.f, 0.f), p1 = make_float2(1.f, 0.f);
 #pragma unroll
                     for (int l = 0; l < M; ++l) {
-                        const float2 *Z = lds + ((size_t)l * P::FPW + s) * P::PS;
+                        const float2 *Z = lds + ((size_t)l * P::FPW + s) * PS;
                         const float2 z = Z[fi], zc = Z[fc];
                         const float2 C0 = make_float2(z.x + zc.x, z.y - zc.y);
                         const float2 C1 = make_float2(z.y + zc.y, zc.x - z.x);
@@ -348,7 +451,7 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
         if (f < NB) {
 #pragma unroll
             for (int l = 0; l < M; ++l) {
-                float2 *Y = lds + (size_t)l * P::FPW * P::PS;
+                float2 *Y = lds + (size_t)l * P::FPW * PS;
                 const float2 y = A[b][l];
                 Y[pad(f)] = make_float2(y.x, -y.y);
                 if (f > 0 && f < D / 2) Y[pad(D - f)] = y;
