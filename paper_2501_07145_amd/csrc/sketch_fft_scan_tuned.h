@@ -19,9 +19,10 @@
 //   then, after one barrier, every thread owns a few frequency bins, separates the two real
 //   transforms of each slot, and advances the accumulators A_1..A_M of its bins by the two
 //   time steps (A_m += A_{m-1}(before the step) * C_m, A_0 = 1).
-//   The rows of the next iteration are fetched into registers while the barrier and the
-//   recurrence run. After the last time step, wavefront m transforms A_m back and writes
-//   block m of the row.
+//   After the last time step, wavefront m transforms A_m back and writes block m of the row.
+//   (Fetching the next iteration's rows early was tried: the 32 extra live registers cost more
+//   in occupancy or spills than the hidden latency gains; workgroups of other sequences on the
+//   same CU hide it instead.)
 //
 // The increments arrive pre-multiplied by 1/2 (done by the producing kernel), which is the
 // factor of the two-for-one separation  C0 = (Z[f] + conj Z[D-f]) / 2,  C1 = (Z[f] - conj Z[D-f]) / 2i.
@@ -110,13 +111,7 @@ __host__ __device__ inline TableLayout table_layout(int D, int G, int LOADB, int
 }
 constexpr uint32_t kFoldPad = 0xffffu;
 constexpr int kFoldInRegs = 8;
-#ifndef RFSF_WAVES_R16
-#define RFSF_WAVES_R16 4
-#endif
-#ifndef RFSF_PREFETCH
-#define RFSF_PREFETCH 0
-#endif
-constexpr bool kPrefetch = RFSF_PREFETCH != 0;   // fetch the next iteration's rows before the barrier      // fold rounds whose entries are fetched with the other tables
+      // fold rounds whose entries are fetched with the other tables
 
 // cos(k pi / 16), k = 0..8
 __device__ constexpr float kCos16[9] = {1.0f, 0.98078528040323043f, 0.92387953251128674f, 0.83146961230254524f,
@@ -299,7 +294,7 @@ struct WaveFft {
 };
 
 template <int LOG2D, int M>
-__global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::LOG2R == 4 ? RFSF_WAVES_R16 : 2, 4))) void sketch_fft_scan_kernel(
+__global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::LOG2R == 4 ? 4 : 2, 4))) void sketch_fft_scan_kernel(
     const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L, int F,
     float *__restrict__ out, int64_t ld_out)
 {
@@ -344,28 +339,37 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
             const int64_t k0 = 2 * (pair0 + s);
             const int64_t kk0 = k0 < T ? k0 : T - 1, kk1 = k0 + 1 < T ? k0 + 1 : T - 1;
             const float *r0 = seq + kk0 * rf + a0, *r1 = seq + kk1 * rf + a0;
-            const float z0 = k0 < T ? 1.f : 0.f, z1 = k0 + 1 < T ? 1.f : 0.f;
 #pragma unroll
-            for (int b = 0; b < P::LOADB; ++b) val[b][s] = make_float2(r0[lane + 64 * b] * z0, r1[lane + 64 * b] * z1);
+            for (int b = 0; b < P::LOADB; ++b) val[b][s] = make_float2(r0[lane + 64 * b], r1[lane + 64 * b]);
+            if (k0 + 1 >= T) {                      // wavefront-uniform: only in the last iteration
+#pragma unroll
+                for (int b = 0; b < P::LOADB; ++b) {
+                    val[b][s].y = 0.f;
+                    if (k0 >= T) val[b][s].x = 0.f;
+                }
+            }
         }
     };
     // Signs applied, values written to the staging areas (natural coordinate order).
     auto stage = [&](int a0, uint32_t sign_word) {
+        // wavefront-uniform: no lane runs past 2F (measured: pays off when a wavefront stages several
+        // pairs, costs 10 % when it stages one, so it is used for FPW > 1 only)
+        const bool full = P::FPW > 1 && a0 + 64 * P::LOADB <= twoF;
 #pragma unroll
         for (int s = 0; s < P::FPW; ++s) {
             float2 *dst = wave_lds + s * PS + a0 + lane;
 #pragma unroll
             for (int b = 0; b < P::LOADB; ++b) {
                 const uint32_t sgn = (sign_word << (31 - b)) & 0x80000000u;
-                if (a0 + 64 * b + lane < twoF)
-                    dst[64 * b] = make_float2(__uint_as_float(__float_as_uint(val[b][s].x) ^ sgn),
-                                              __uint_as_float(__float_as_uint(val[b][s].y) ^ sgn));
+                const float2 x = make_float2(__uint_as_float(__float_as_uint(val[b][s].x) ^ sgn),
+                                             __uint_as_float(__float_as_uint(val[b][s].y) ^ sgn));
+                if (full) dst[64 * b] = x;
+                else if (a0 + 64 * b + lane < twoF) dst[64 * b] = x;
             }
         }
     };
 
     const int64_t pairs = (T + 1) / 2;
-    if (kPrefetch) fetch(0, 0);
     for (int64_t pair0 = 0; pair0 < pairs; pair0 += P::FPW) {
         // Tables of this level. They are the same every iteration and stay in L1/L2; the pointer is
         // laundered so that the compiler reloads them here instead of keeping ~90 loop-invariant
@@ -379,8 +383,8 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
         for (int g = 0; g < kFoldInRegs; ++g) fw[g] = g < NG ? tabi[tl.fold + g * P::G + lg] : kFoldPad << 16;
         const uint32_t sw0 = tabi[tl.signs + lane];
 
-        // 1a. staging: the prefetched first batch, then any further batches
-        if (!kPrefetch) fetch(pair0, 0);
+        // 1a. staging, one batch of 64*LOADB coordinates at a time
+        fetch(pair0, 0);
         stage(0, sw0);
         for (int bi = 1; bi < tl.nbatch; ++bi) {
             const int a0 = bi * 64 * P::LOADB;
@@ -414,8 +418,6 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
         }
         // 2. FPW transforms per wavefront, in place in the slots
         fft.run_from_registers(my_slot, v);
-        // rows of the next iteration: in flight during the barrier and the recurrence
-        if (kPrefetch && pair0 + P::FPW < pairs) fetch(pair0 + P::FPW, 0);
         __syncthreads();
         // 3. per-bin separation and recurrence, two time steps per slot, levels ascending
 #pragma unroll
