@@ -28,7 +28,84 @@ __device__ __forceinline__ void sincos_reduced(float x, float &s, float &c)
     c = __uint_as_float(__float_as_uint(cc) ^ ((((unsigned)q + 1u) & 2u) << 30));
 }
 
+// The same, times `scale`, with the scale folded into the polynomial coefficients (no extra
+// multiplies): sc = {scale, -scale/2, scale*c1, scale*c2, scale*c3} for the cosine, and the sine
+// polynomial is evaluated on r*scale.
+struct ScaledCoeffs { float one, half, c1, c2, c3; };
+__device__ __forceinline__ ScaledCoeffs scaled_coeffs(float scale)
+{
+    return {scale, -0.5f * scale, 4.166664568298827e-2f * scale, -1.388731625493765e-3f * scale,
+            2.443315711809948e-5f * scale};
+}
+__device__ __forceinline__ void sincos_scaled(float x, const ScaledCoeffs &k, float &s, float &c)
+{
+    const float kf = rintf(x * 0.636619772367581343f);
+    float r = fmaf(-kf, 1.57079637050628662109375f, x);
+    r = fmaf(-kf, -4.37113900018624283e-8f, r);
+    const float r2 = r * r;
+    const float rs = r * k.one;
+    const float ps = fmaf(r2, fmaf(r2, -1.9515295891e-4f, 8.3321608736e-3f), -1.6666654611e-1f);
+    const float S = fmaf(rs * r2, ps, rs);
+    const float pc = fmaf(r2, fmaf(r2, k.c3, k.c2), k.c1);
+    const float C = fmaf(r2 * r2, pc, fmaf(k.half, r2, k.one));
+    const int q = (int)kf;
+    const float ss = (q & 1) ? C : S;
+    const float cc = (q & 1) ? S : C;
+    s = __uint_as_float(__float_as_uint(ss) ^ (((unsigned)q & 2u) << 30));
+    c = __uint_as_float(__float_as_uint(cc) ^ ((((unsigned)q + 1u) & 2u) << 30));
+}
+
 constexpr int kRowsPerTile = 32;
+
+// Epilogue shared by the matrix-core kernels: sin/cos of the 16 angles a lane holds (rows
+// 8q + 4*half + i of the tile, one frequency), their time difference and the stores, one block of
+// four rows at a time so that stores are spread between the arithmetic. The row above a block comes
+// from the partner half-wavefront (its block q for the upper half, q-1 for the lower half) or, for
+// the first block of the lower half, from the previous tile (carry). In a full interior tile the
+// stores are unconditional and addressed as scalar base + 32-bit lane offset.
+template <typename AngleOf>
+__device__ __forceinline__ void sincos_difference_store(
+    AngleOf angle, const ScaledCoeffs &coeffs, float &carry_c, float &carry_s, int half, bool f_ok, int nrow,
+    int64_t gt, int64_t g0, int64_t rf, int F, float *__restrict__ level_base, int f)
+{
+    const bool interior = nrow == kRowsPerTile && gt > g0;      // wavefront-uniform
+    float *cos_base = level_base + (gt - 1) * rf;               // uniform
+    float *sin_base = cos_base + F;
+    const uint32_t lane_off = (uint32_t)f + (uint32_t)(4 * half) * (uint32_t)rf;
+    float below_c = carry_c, below_s = carry_s;                 // lower half: partner's previous block
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        float cs[4], sn[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sincos_scaled(angle(4 * q + i), coeffs, sn[i], cs[i]);
+        const float pc = __shfl_xor(cs[3], 32), ps = __shfl_xor(sn[3], 32);
+        const float up_c = half ? pc : below_c, up_s = half ? ps : below_s;
+        below_c = pc;
+        below_s = ps;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float dc = cs[i] - (i ? cs[i - 1] : up_c);
+            const float ds = sn[i] - (i ? sn[i - 1] : up_s);
+            if (interior) {
+                if (f_ok) {
+                    const uint32_t off = lane_off + (uint32_t)(8 * q + i) * (uint32_t)rf;
+                    cos_base[off] = dc;
+                    sin_base[off] = ds;
+                }
+            } else {
+                const int r = 8 * q + 4 * half + i;
+                const int64_t g = gt + r;
+                if (f_ok && r < nrow && g > g0) {
+                    float *dst = level_base + f + (g - 1) * rf;
+                    dst[0] = dc;
+                    dst[F] = ds;
+                }
+            }
+        }
+    }
+    carry_c = below_c;      // row 31 of this tile as seen by the lower half (unused by the upper half)
+    carry_s = below_s;
+}
 
 // Generic vector-ALU kernel: one thread per frequency, a workgroup walks a range of
 // flattened rows (n * L + t) and carries the previous row's features in registers.
@@ -84,18 +161,25 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 template <int KSTEPS>     // ceil(d / 2) padded: channels 2*KSTEPS
 __global__ __launch_bounds__(256) void rff_increments_mfma(
     const float *__restrict__ X, const float *__restrict__ W, float inv_lengthscale, float scale,
-    int64_t rows, int d, int M, int F, int64_t rows_per_block, float *__restrict__ dphi)
+    int64_t rows, int d, int M, int F, int64_t rows_per_block, int64_t nblk, int slab_fastest,
+    float *__restrict__ dphi)
 {
     constexpr int KP = 2 * KSTEPS;              // padded channel count
     constexpr int XS = KP | 1;                  // odd LDS row stride: conflict-free A reads
-    __shared__ float xs[kRowsPerTile * XS];
+    __shared__ float xs[2 * kRowsPerTile * XS];
+    // Block order. With many (level, frequency slab) pairs per row range the slab index runs fastest:
+    // the workgroups that write the same rows are dispatched together, which keeps the writes of one
+    // DRAM page close in time. With few of them the row range runs fastest.
     const int fblocks = (F + 127) / 128;
-    const int m = blockIdx.y / fblocks;
+    const int nslab = M * fblocks;
+    const int slab = slab_fastest ? (int)(blockIdx.x % nslab) : (int)(blockIdx.x / nblk);
+    const int64_t range = slab_fastest ? blockIdx.x / nslab : blockIdx.x % nblk;
+    const int m = slab / fblocks;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, col = lane & 31;
-    const int f = (blockIdx.y % fblocks) * 128 + wave * 32 + col;     // this lane's frequency
+    const int f = (slab % fblocks) * 128 + wave * 32 + col;           // this lane's frequency
     const bool f_ok = f < F;
-    const int64_t g0 = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t g0 = range * rows_per_block;
     const int64_t g1 = min(rows - 1, g0 + rows_per_block);             // last row whose phi we need
     const int64_t rf = (int64_t)M * 2 * F;
 
@@ -107,52 +191,48 @@ __global__ __launch_bounds__(256) void rff_increments_mfma(
         breg[kk] = (f_ok && k < d) ? W[((int64_t)m * d + k) * F + f] * inv_lengthscale : 0.f;
     }
     float carry_c = 0.f, carry_s = 0.f;         // row 31 of the previous tile (lower half-wavefront)
-    float *out_base = dphi + (int64_t)m * 2 * F + f;
+    float *level_base = dphi + (int64_t)m * 2 * F;     // uniform; the lane's frequency is added per store
+    const ScaledCoeffs coeffs = scaled_coeffs(scale);
 
-    for (int64_t gt = g0; gt <= g1; gt += kRowsPerTile) {
+    // X tiles are double-buffered in LDS: the next tile's rows are fetched into registers before the
+    // current tile is processed and written to the other buffer afterwards (one barrier per tile).
+    constexpr int NX = (kRowsPerTile * KP + 255) / 256;
+    float xr[NX];
+    auto fetch_tile = [&](int64_t gt) {
         const int nrow = (int)min((int64_t)kRowsPerTile, g1 - gt + 1);
-        __syncthreads();
-        for (int i = threadIdx.x; i < kRowsPerTile * KP; i += 256) {
+#pragma unroll
+        for (int u = 0; u < NX; ++u) {
+            const int i = threadIdx.x + 256 * u;
             const int r = i / KP, c = i - r * KP;
-            xs[r * XS + c] = (r < nrow && c < d) ? X[(gt + r) * d + c] : 0.f;
+            xr[u] = (i < kRowsPerTile * KP && r < nrow && c < d) ? X[(gt + r) * d + c] : 0.f;
         }
-        __syncthreads();
+    };
+    auto put_tile = [&](float *buf) {
+#pragma unroll
+        for (int u = 0; u < NX; ++u) {
+            const int i = threadIdx.x + 256 * u;
+            const int r = i / KP, c = i - r * KP;
+            if (i < kRowsPerTile * KP) buf[r * XS + c] = xr[u];
+        }
+    };
+    fetch_tile(g0);
+    put_tile(xs);
+    __syncthreads();
+    int cur = 0;
+    for (int64_t gt = g0; gt <= g1; gt += kRowsPerTile, cur ^= 1) {
+        const int nrow = (int)min((int64_t)kRowsPerTile, g1 - gt + 1);
+        const bool more = gt + kRowsPerTile <= g1;
+        if (more) fetch_tile(gt + kRowsPerTile);
+        const float *xt = xs + cur * (kRowsPerTile * XS);
         floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk)
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xs[col * XS + 2 * kk + half], breg[kk], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xt[col * XS + 2 * kk + half], breg[kk], acc, 0, 0, 0);
 
-        float cs[16], sn[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            sincos_reduced(acc[v], sn[v], cs[v]);
-            cs[v] *= scale;
-            sn[v] *= scale;
-        }
-        // value of the row just above each 4-row block: from the partner half-wavefront
-        float up_c[4], up_s[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float pc = __shfl_xor(cs[4 * q + 3], 32);
-            const float ps = __shfl_xor(sn[4 * q + 3], 32);
-            // upper half needs rows 8q+3 (partner's block q); lower half needs rows 8q-1
-            // (partner's block q-1, or the previous tile for q = 0)
-            if (half) { up_c[q] = pc; up_s[q] = ps; }
-            else if (q < 3) { up_c[q + 1] = pc; up_s[q + 1] = ps; }
-            if (q == 3 && !half) { up_c[0] = carry_c; up_s[0] = carry_s; carry_c = pc; carry_s = ps; }
-        }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = 8 * (v >> 2) + 4 * half + (v & 3);
-            const float prev_c = (v & 3) ? cs[v - 1] : up_c[v >> 2];
-            const float prev_s = (v & 3) ? sn[v - 1] : up_s[v >> 2];
-            const int64_t g = gt + r;
-            if (f_ok && r < nrow && g > g0) {
-                float *dst = out_base + (g - 1) * rf;
-                dst[0] = cs[v] - prev_c;
-                dst[F] = sn[v] - prev_s;
-            }
-        }
+        sincos_difference_store([&](int v) { return acc[v]; }, coeffs, carry_c, carry_s, half, f_ok, nrow, gt, g0,
+                                rf, F, level_base, f);
+        if (more) put_tile(xs + (cur ^ 1) * (kRowsPerTile * XS));
+        __syncthreads();
     }
 }
 
@@ -173,19 +253,23 @@ __device__ __forceinline__ float bf16_value(uint32_t b) { return __uint_as_float
 template <int KSTEPS>     // ceil(d / 16): channels padded to 16*KSTEPS
 __global__ __launch_bounds__(256) void rff_increments_mfma_bf16(
     const float *__restrict__ X, const float *__restrict__ W, float inv_lengthscale, float scale,
-    int64_t rows, int d, int M, int F, int64_t rows_per_block, float *__restrict__ dphi)
+    int64_t rows, int d, int M, int F, int64_t rows_per_block, int64_t nblk, int slab_fastest,
+    float *__restrict__ dphi)
 {
     constexpr int KP = 16 * KSTEPS;
     constexpr int XS = KP + 8;                  // bf16 elements per LDS row (16-byte padded)
     __shared__ __attribute__((aligned(16))) uint16_t xhi[kRowsPerTile * XS];
     __shared__ __attribute__((aligned(16))) uint16_t xlo[kRowsPerTile * XS];
-    const int fblocks = (F + 127) / 128;
-    const int m = blockIdx.y / fblocks;
+    const int fblocks = (F + 127) / 128;                              // same block order as the fp32 kernel
+    const int nslab = M * fblocks;
+    const int slab = slab_fastest ? (int)(blockIdx.x % nslab) : (int)(blockIdx.x / nblk);
+    const int64_t range = slab_fastest ? blockIdx.x / nslab : blockIdx.x % nblk;
+    const int m = slab / fblocks;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, col = lane & 31;
-    const int f = (blockIdx.y % fblocks) * 128 + wave * 32 + col;
+    const int f = (slab % fblocks) * 128 + wave * 32 + col;
     const bool f_ok = f < F;
-    const int64_t g0 = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t g0 = range * rows_per_block;
     const int64_t g1 = min(rows - 1, g0 + rows_per_block);
     const int64_t rf = (int64_t)M * 2 * F;
 
@@ -204,7 +288,8 @@ __global__ __launch_bounds__(256) void rff_increments_mfma_bf16(
         breg[kk] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
     }
     float carry_c = 0.f, carry_s = 0.f;
-    float *out_base = dphi + (int64_t)m * 2 * F + f;
+    float *level_base = dphi + (int64_t)m * 2 * F;     // uniform; the lane's frequency is added per store
+    const ScaledCoeffs coeffs = scaled_coeffs(scale);
 
     for (int64_t gt = g0; gt <= g1; gt += kRowsPerTile) {
         const int nrow = (int)min((int64_t)kRowsPerTile, g1 - gt + 1);
@@ -225,34 +310,8 @@ __global__ __launch_bounds__(256) void rff_increments_mfma_bf16(
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, breg[kk], acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, breg[kk], acc, 0, 0, 0);
         }
-        float cs[16], sn[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            sincos_reduced(acc[v] * inv_lengthscale, sn[v], cs[v]);
-            cs[v] *= scale;
-            sn[v] *= scale;
-        }
-        float up_c[4], up_s[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float pc = __shfl_xor(cs[4 * q + 3], 32);
-            const float ps = __shfl_xor(sn[4 * q + 3], 32);
-            if (half) { up_c[q] = pc; up_s[q] = ps; }
-            else if (q < 3) { up_c[q + 1] = pc; up_s[q + 1] = ps; }
-            if (q == 3 && !half) { up_c[0] = carry_c; up_s[0] = carry_s; carry_c = pc; carry_s = ps; }
-        }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = 8 * (v >> 2) + 4 * half + (v & 3);
-            const float prev_c = (v & 3) ? cs[v - 1] : up_c[v >> 2];
-            const float prev_s = (v & 3) ? sn[v - 1] : up_s[v >> 2];
-            const int64_t g = gt + r;
-            if (f_ok && r < nrow && g > g0) {
-                float *dst = out_base + (g - 1) * rf;
-                dst[0] = cs[v] - prev_c;
-                dst[F] = sn[v] - prev_s;
-            }
-        }
+        sincos_difference_store([&](int v) { return acc[v] * inv_lengthscale; }, coeffs, carry_c, carry_s, half,
+                                f_ok, nrow, gt, g0, rf, F, level_base, f);
     }
 }
 
@@ -264,15 +323,19 @@ hipError_t launch_rff_increments(const float *X, const float *W, float inv_lengt
 {
     const int64_t rows = n_seq * L;
     if (rows < 2) return hipSuccess;
-    const int64_t rows_per_block = 255;     // 256 rows of phi = eight tiles; consecutive blocks share one row
+    // 255 increments per workgroup: 256 rows of phi = eight tiles; consecutive workgroups share one row.
+    // (Shorter ranges for small problems were tried and were slower.)
+    const int64_t rows_per_block = 255;
     const int64_t nblk = (rows - 1 + rows_per_block - 1) / rows_per_block;
     const float scale = 0.5f / sqrtf((float)F);    // the consumer's two-for-one FFT wants halved increments
+    if (nblk * M * ((F + 127) / 128) > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int slab_fastest = M * ((F + 127) / 128) >= 8;
     if (bf16) {            // the caller (API layer) has checked d <= 128
         const int fb = (F + 127) / 128;
-        dim3 grid((unsigned)nblk, (unsigned)(M * fb));
+        dim3 grid((unsigned)(nblk * M * fb));
 #define RFSF_LAUNCH_BF16(KS)                                                                                   \
     hipLaunchKernelGGL(rff_increments_mfma_bf16<KS>, grid, dim3(256), 0, stream, X, W, inv_lengthscale, scale, \
-                       rows, d, M, F, rows_per_block, dphi)
+                       rows, d, M, F, rows_per_block, nblk, slab_fastest, dphi)
         if (d <= 16) RFSF_LAUNCH_BF16(1);
         else if (d <= 32) RFSF_LAUNCH_BF16(2);
         else if (d <= 64) RFSF_LAUNCH_BF16(4);
@@ -282,10 +345,10 @@ hipError_t launch_rff_increments(const float *X, const float *W, float inv_lengt
     }
     if (d <= 64) {
         const int fb = (F + 127) / 128;
-        dim3 grid((unsigned)nblk, (unsigned)(M * fb));
+        dim3 grid((unsigned)(nblk * M * fb));
 #define RFSF_LAUNCH_MFMA(KS)                                                                              \
     hipLaunchKernelGGL(rff_increments_mfma<KS>, grid, dim3(256), 0, stream, X, W, inv_lengthscale, scale, \
-                       rows, d, M, F, rows_per_block, dphi)
+                       rows, d, M, F, rows_per_block, nblk, slab_fastest, dphi)
         if (d <= 4) RFSF_LAUNCH_MFMA(2);
         else if (d <= 8) RFSF_LAUNCH_MFMA(4);
         else if (d <= 18) RFSF_LAUNCH_MFMA(9);

@@ -128,8 +128,9 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
         return rfsf::launch_fill_trivial(out, shape->N, shape->ld_out, ncols, stream) == hipSuccess
                    ? RFSF_OK : RFSF_E_HIP;
     }
-    if ((int64_t)shape->M * ((shape->F + 127) / 128) > 65535) return RFSF_E_UNSUPPORTED;
+    if ((int64_t)shape->M * ((shape->F + 127) / 128) > 65535) return RFSF_E_UNSUPPORTED;   // grid limits
     if (shape->rff_bf16 != 0 && shape->d > 128) return RFSF_E_UNSUPPORTED;
+    if ((int64_t)shape->M * 2 * shape->F > ((int64_t)1 << 26)) return RFSF_E_UNSUPPORTED;   // 32-bit row offsets
     if (!workspace) return RFSF_E_NULLPTR;
     int64_t chunk = chunk_for(shape, workspace_bytes);
     if (chunk < 1) return RFSF_E_WORKSPACE_TOO_SMALL;

@@ -129,8 +129,9 @@ __global__ __launch_bounds__(256) void build_tables_kernel(
     const int32_t *__restrict__ hash, const float *__restrict__ sign, int twoF, int D, int G, int LOADB,
     int PD, uint32_t *__restrict__ table)
 {
-    extern __shared__ int table_scratch[];
-    int *h = table_scratch, *rk = h + twoF, *cls = rk + twoF, *src0 = cls + twoF + 1, *src1 = src0 + D;
+    extern __shared__ __attribute__((aligned(16))) int table_scratch[];
+    const int tf4 = (twoF + 3) & ~3;              // keeps the arrays 16-byte aligned
+    int *h = table_scratch, *rk = h + tf4, *cls = rk + tf4, *src0 = cls + tf4 + 4, *src1 = src0 + D;
     __shared__ int max_rank, n_rounds;
     const int m = blockIdx.x, tid = threadIdx.x;
     const tuned::TableLayout tl = tuned::table_layout(D, G, LOADB, twoF);
@@ -143,8 +144,13 @@ __global__ __launch_bounds__(256) void build_tables_kernel(
     if (tid == 0) max_rank = 0;
     __syncthreads();
     for (int a = tid; a < twoF; a += 256) {
-        int r = 0;
-        for (int a2 = 0; a2 < a; ++a2) r += h[a2] == h[a];
+        const int ha = h[a];
+        int r = 0, a2 = 0;
+        for (; a2 + 8 <= a; a2 += 8) {              // wide LDS reads keep the loop off the LDS latency
+            const int4 u = *reinterpret_cast<const int4 *>(h + a2), w = *reinterpret_cast<const int4 *>(h + a2 + 4);
+            r += (u.x == ha) + (u.y == ha) + (u.z == ha) + (u.w == ha) + (w.x == ha) + (w.y == ha) + (w.z == ha) + (w.w == ha);
+        }
+        for (; a2 < a; ++a2) r += h[a2] == ha;
         rk[a] = r;
         if (r == 0) src0[h[a]] = a;
         else if (r == 1) src1[h[a]] = a;
@@ -181,8 +187,12 @@ __global__ __launch_bounds__(256) void build_tables_kernel(
     for (int a = tid; a < twoF; a += 256) {
         const int r = rk[a];
         if (r < 2) continue;
-        int idx = 0;
-        for (int a2 = 0; a2 < a; ++a2) idx += rk[a2] == r;
+        int idx = 0, a2 = 0;
+        for (; a2 + 8 <= a; a2 += 8) {
+            const int4 u = *reinterpret_cast<const int4 *>(rk + a2), w = *reinterpret_cast<const int4 *>(rk + a2 + 4);
+            idx += (u.x == r) + (u.y == r) + (u.z == r) + (u.w == r) + (w.x == r) + (w.y == r) + (w.z == r) + (w.w == r);
+        }
+        for (; a2 < a; ++a2) idx += rk[a2] == r;
         tab[tl.fold + cls[r] + idx] = ((uint32_t)a * 8u) | (((uint32_t)src0[h[a]] * 8u) << 16);
     }
 }
@@ -251,7 +261,7 @@ hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int
     TunedGeometry g;
     if (!sketch_fft_scan_is_tuned(M, F, D) || !tuned_geometry(D, &g)) return hipSuccess;   // generic kernel: no table
     const int twoF = 2 * F;
-    const size_t lds = sizeof(int) * (size_t)(3 * twoF + 1 + 2 * D);
+    const size_t lds = sizeof(int) * (size_t)(3 * ((twoF + 3) & ~3) + 4 + 2 * D);
     if (lds > 64 * 1024) {
         static size_t granted = 0;
         if (lds > granted) {
