@@ -258,8 +258,8 @@ __global__ __launch_bounds__(256) void rff_increments_mfma_bf16(
 {
     constexpr int KP = 16 * KSTEPS;
     constexpr int XS = KP + 8;                  // bf16 elements per LDS row (16-byte padded)
-    __shared__ __attribute__((aligned(16))) uint16_t xhi[kRowsPerTile * XS];
-    __shared__ __attribute__((aligned(16))) uint16_t xlo[kRowsPerTile * XS];
+    __shared__ __attribute__((aligned(16))) uint16_t xhi[2 * kRowsPerTile * XS];
+    __shared__ __attribute__((aligned(16))) uint16_t xlo[2 * kRowsPerTile * XS];
     const int fblocks = (F + 127) / 128;                              // same block order as the fp32 kernel
     const int nslab = M * fblocks;
     const int slab = slab_fastest ? (int)(blockIdx.x % nslab) : (int)(blockIdx.x / nblk);
@@ -291,27 +291,53 @@ __global__ __launch_bounds__(256) void rff_increments_mfma_bf16(
     float *level_base = dphi + (int64_t)m * 2 * F;     // uniform; the lane's frequency is added per store
     const ScaledCoeffs coeffs = scaled_coeffs(scale);
 
-    for (int64_t gt = g0; gt <= g1; gt += kRowsPerTile) {
+    // double-buffered X tiles, as in the fp32 kernel; the split into two bf16 terms happens when a
+    // tile is written to LDS
+    constexpr int NX = (kRowsPerTile * KP + 255) / 256;
+    constexpr int TILE = kRowsPerTile * XS;
+    float xr[NX];
+    auto fetch_tile = [&](int64_t gt) {
         const int nrow = (int)min((int64_t)kRowsPerTile, g1 - gt + 1);
-        __syncthreads();
-        for (int i = threadIdx.x; i < kRowsPerTile * KP; i += 256) {
+#pragma unroll
+        for (int u = 0; u < NX; ++u) {
+            const int i = threadIdx.x + 256 * u;
             const int r = i / KP, c = i - r * KP;
-            const float x = (r < nrow && c < d) ? X[(gt + r) * d + c] : 0.f;
-            const uint32_t hi = bf16_bits(x);
-            xhi[r * XS + c] = (uint16_t)hi;
-            xlo[r * XS + c] = (uint16_t)bf16_bits(x - bf16_value(hi));
+            xr[u] = (i < kRowsPerTile * KP && r < nrow && c < d) ? X[(gt + r) * d + c] : 0.f;
         }
-        __syncthreads();
+    };
+    auto put_tile = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < NX; ++u) {
+            const int i = threadIdx.x + 256 * u;
+            const int r = i / KP, c = i - r * KP;
+            if (i < kRowsPerTile * KP) {
+                const uint32_t hi = bf16_bits(xr[u]);
+                xhi[buf * TILE + r * XS + c] = (uint16_t)hi;
+                xlo[buf * TILE + r * XS + c] = (uint16_t)bf16_bits(xr[u] - bf16_value(hi));
+            }
+        }
+    };
+    fetch_tile(g0);
+    put_tile(0);
+    __syncthreads();
+    int cur = 0;
+    for (int64_t gt = g0; gt <= g1; gt += kRowsPerTile, cur ^= 1) {
+        const int nrow = (int)min((int64_t)kRowsPerTile, g1 - gt + 1);
+        const bool more = gt + kRowsPerTile <= g1;
+        if (more) fetch_tile(gt + kRowsPerTile);
         floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) {
-            const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&xhi[col * XS + 16 * kk + 8 * half]));
-            const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&xlo[col * XS + 16 * kk + 8 * half]));
+            const int at = cur * TILE + col * XS + 16 * kk + 8 * half;
+            const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&xhi[at]));
+            const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&xlo[at]));
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, breg[kk], acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, breg[kk], acc, 0, 0, 0);
         }
         sincos_difference_store([&](int v) { return acc[v] * inv_lengthscale; }, coeffs, carry_c, carry_s, half,
                                 f_ok, nrow, gt, g0, rf, F, level_base, f);
+        if (more) put_tile(cur ^ 1);
+        __syncthreads();
     }
 }
 
