@@ -29,6 +29,19 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 MFMA_FP32_PEAK_TFLOPS = 157.3    # MI355X dense fp32 matrix, published
 
+# HBM bytes per kernel launch measured with rocprofv3 (FETCH_SIZE * 2.000 + WRITE_SIZE * 1.000 KiB, the
+# factors calibrated on a plain 1 GiB device copy in the same run; summaries: profiles/hbm_traffic_*.txt).
+# These are measurements of the kernels as committed with those summaries, not computed here; a workload
+# without an entry reports null.
+MEASURED_TRAFFIC_KIB = {
+    ("small", "rff_increments"): 6554.3 * 2 + 399996.0,
+    ("small", "sketch_fft_scan"): 198139.7 * 2 + 4031.2,
+    ("small", "gram"): 16101.4 * 2 + 3906.2,
+    ("medium", "rff_increments"): 295739.7 * 2 + 19999980.0,
+    ("medium", "sketch_fft_scan"): 10666862.6 * 2 + 193906.5,
+    ("medium", "gram"): 12392838.8 * 2 + 420021.2,
+}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -38,6 +51,9 @@ def main() -> int:
     ap.add_argument("--workload", default="small", choices=["tiny", "small", "medium", "long", "large"])
     ap.add_argument("--cpu-rows", type=int, default=-1, help="oracle sample size (-1: per-workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="after the timed steps run one plain device copy of this many MiB (calibrates the "
+                         "FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (sequences are independent; sharding N over "
@@ -91,6 +107,13 @@ def main() -> int:
     prof = rfsf.rfsf_ts_profile_read(reset=True)
     rfsf.rfsf_ts_profile_enable(False)
 
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib * (1 << 18), dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     units = (w.N + w.N2) * w.L                       # sequence-steps per step
     incr_bytes_per_unit = 4.0 * w.M * 2 * w.F          # fp32 increments written by one kernel, read by the next
     n_seq = w.N + w.N2
@@ -103,8 +126,10 @@ def main() -> int:
         avg_ms = prof[f"ms_{name}"] / n
         per_launch = work_per_step * args.steps / n
         achieved = per_launch / (avg_ms * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+        kib = MEASURED_TRAFFIC_KIB.get((w.name, name))
         kernels[name] = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                         "frac": achieved / peak, "traffic": None, "avg_launch_ms": avg_ms,
+                         "frac": achieved / peak, "traffic": None if kib is None else kib * 1024.0,
+                         "algorithmic_per_launch": per_launch, "avg_launch_ms": avg_ms,
                          "launches_per_step": n / args.steps, "ms_per_step": prof[f"ms_{name}"] / args.steps}
 
     entry("rff_increments", "hbm", units * (4.0 * w.d + incr_bytes_per_unit), "GB/s", HBM_PEAK_GBS)
