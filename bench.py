@@ -135,7 +135,10 @@ def main() -> int:
     entry("rff_increments", "hbm", units * (4.0 * w.d + incr_bytes_per_unit), "GB/s", HBM_PEAK_GBS)
     entry("sketch_fft_scan", "hbm", units * incr_bytes_per_unit + 4.0 * n_seq * w.M * w.D, "GB/s", HBM_PEAK_GBS)
     Ny = w.N2 if w.N2 else w.N
-    entry("gram", "mfma", 2.0 * w.N * Ny * w.ncols, "TFLOP/s", MFMA_FP32_PEAK_TFLOPS)
+    # flops the kernel performs: the whole matrix for a cross Gram; for K = Phi Phi^T of 2048+ rows
+    # only the tiles on or above the diagonal (counted here as N(N+1)/2 inner products)
+    gram_pairs = w.N * Ny if (w.N2 or ((w.N + 63) // 64) * ((w.N + 63) // 64 + 1) // 2 < 512) else w.N * (w.N + 1) / 2
+    entry("gram", "mfma", 2.0 * gram_pairs * w.ncols, "TFLOP/s", MFMA_FP32_PEAK_TFLOPS)
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     roofline = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
     roofline["kernel"] = dominant

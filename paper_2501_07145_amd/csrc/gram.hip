@@ -59,7 +59,9 @@ constexpr int kLdsStride = kKT + 4; // floats per LDS row: 16 consecutive rows s
 // MFMA k-step kk of a slab uses the physical columns kk (lanes 0-31) and kk + 16 (lanes 32-63),
 // the same for both operands, so that each lane reads 16 consecutive floats of its row.
 // Needs 16-byte aligned bases and leading dimensions that are multiples of 4.
-template <int WT>
+// SYM: PhiY is PhiX. Only the tiles on or above the diagonal are computed (blockIdx.x enumerates
+// them row by row); mirror_lower_kernel fills in the rest afterwards.
+template <int WT, bool SYM>
 __global__ __launch_bounds__(256) void gram_mfma(
     const float *__restrict__ A, int64_t Nx, int64_t lda, const float *__restrict__ B, int64_t Ny,
     int64_t ldb, int64_t K, float *__restrict__ C, int64_t ldc)
@@ -71,7 +73,15 @@ __global__ __launch_bounds__(256) void gram_mfma(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
     const int wi = wave >> 1, wj = wave & 1;
-    const int64_t i0 = (int64_t)blockIdx.y * TILE, j0 = (int64_t)blockIdx.x * TILE;
+    int64_t bi = blockIdx.y, bj = blockIdx.x;
+    if (SYM) {      // linear index over the upper triangle of an nt x nt tile grid -> (bi, bj >= bi)
+        const int64_t nt = (Nx + TILE - 1) / TILE, idx = blockIdx.x;
+        bi = (int64_t)(((double)(2 * nt + 1) - sqrt((double)(2 * nt + 1) * (double)(2 * nt + 1) - 8.0 * (double)idx)) * 0.5);
+        while (bi > 0 && bi * nt - bi * (bi - 1) / 2 > idx) --bi;                 // start of row bi
+        while ((bi + 1) * nt - (bi + 1) * bi / 2 <= idx) ++bi;
+        bj = bi + (idx - (bi * nt - bi * (bi - 1) / 2));
+    }
+    const int64_t i0 = bi * TILE, j0 = bj * TILE;
 
     floatx16 acc[WT][WT];
 #pragma unroll
@@ -154,6 +164,25 @@ __global__ __launch_bounds__(256) void gram_mfma(
         }
 }
 
+// Copies the part of a symmetric matrix above the diagonal to the part below it, 32x32 tiles
+// transposed through LDS so that both the reads and the writes are coalesced.
+__global__ __launch_bounds__(256) void mirror_lower_kernel(float *__restrict__ C, int64_t N, int64_t ldc)
+{
+    __shared__ float t[32][33];
+    const int64_t ti = blockIdx.y, tj = blockIdx.x;
+    if (tj < ti) return;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int r = ty; r < 32; r += 8) {
+        const int64_t i = ti * 32 + r, j = tj * 32 + tx;
+        t[r][tx] = (i < N && j < N) ? C[i * ldc + j] : 0.f;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int64_t i = tj * 32 + r, j = ti * 32 + tx;       // destination (i, j) = source (j, i)
+        if (i < N && j < N && i > j) C[i * ldc + j] = t[tx][r];
+    }
+}
+
 }  // namespace
 
 hipError_t launch_gram(const float *PhiX, int64_t Nx, int64_t ldx, const float *PhiY, int64_t Ny,
@@ -164,12 +193,28 @@ hipError_t launch_gram(const float *PhiX, int64_t Nx, int64_t ldx, const float *
                          reinterpret_cast<uintptr_t>(PhiY) % 16 == 0;
     if (aligned) {
         const int64_t big_tiles = ((Nx + 127) / 128) * ((Ny + 127) / 128);
-        if (big_tiles >= 512) {
+        // worth it once the upper triangle alone fills the chip twice over (64-row tiles)
+        const int64_t nt64 = (Nx + 63) / 64;
+        const bool symmetric = PhiX == PhiY && Nx == Ny && ldx == ldy && nt64 * (nt64 + 1) / 2 >= 512;
+        if (symmetric) {        // K = PhiX PhiX^T: upper triangle on the matrix cores, then mirrored
+            const bool big = big_tiles >= 1024;
+            const int64_t nt = (Nx + (big ? 127 : 63)) / (big ? 128 : 64);
+            const int64_t tiles = nt * (nt + 1) / 2;
+            if (tiles > 0x7fffffffLL || (Nx + 31) / 32 > 65535) return hipErrorInvalidValue;
+            if (big)
+                hipLaunchKernelGGL((gram_mfma<2, true>), dim3((unsigned)tiles), dim3(256), 0, stream, PhiX, Nx, ldx,
+                                   PhiY, Ny, ldy, ncols, K, ldk);
+            else
+                hipLaunchKernelGGL((gram_mfma<1, true>), dim3((unsigned)tiles), dim3(256), 0, stream, PhiX, Nx, ldx,
+                                   PhiY, Ny, ldy, ncols, K, ldk);
+            const unsigned nm = (unsigned)((Nx + 31) / 32);
+            hipLaunchKernelGGL(mirror_lower_kernel, dim3(nm, nm), dim3(256), 0, stream, K, Nx, ldk);
+        } else if (big_tiles >= 512) {
             dim3 g((unsigned)((Ny + 127) / 128), (unsigned)((Nx + 127) / 128));
-            hipLaunchKernelGGL(gram_mfma<2>, g, dim3(256), 0, stream, PhiX, Nx, ldx, PhiY, Ny, ldy, ncols, K, ldk);
+            hipLaunchKernelGGL((gram_mfma<2, false>), g, dim3(256), 0, stream, PhiX, Nx, ldx, PhiY, Ny, ldy, ncols, K, ldk);
         } else {
             dim3 g((unsigned)((Ny + 63) / 64), (unsigned)((Nx + 63) / 64));
-            hipLaunchKernelGGL(gram_mfma<1>, g, dim3(256), 0, stream, PhiX, Nx, ldx, PhiY, Ny, ldy, ncols, K, ldk);
+            hipLaunchKernelGGL((gram_mfma<1, false>), g, dim3(256), 0, stream, PhiX, Nx, ldx, PhiY, Ny, ldy, ncols, K, ldk);
         }
         return hipGetLastError();
     }

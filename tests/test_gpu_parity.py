@@ -206,3 +206,19 @@ def test_results_are_bit_reproducible():
     Ka, Kb = rfsf.rfsf_ts_gram(a).clone(), rfsf.rfsf_ts_gram(b).clone()
     torch.cuda.synchronize()
     assert torch.equal(Ka, Kb)
+
+
+@pytest.mark.parametrize("N,C", [(2100, 517), (2049, 64), (4500, 100), (1000, 1025)])
+def test_symmetric_gram_path(oracle, N, C):
+    """K = Phi Phi^T with one operand: only the upper triangle is computed, the rest mirrored."""
+    rng = np.random.default_rng(N + C)
+    ld = (C + 3) // 4 * 4
+    A = rng.standard_normal((N, ld)).astype(np.float32)
+    Ad = torch.from_numpy(A).cuda()[:, :C]
+    K = rfsf.rfsf_ts_gram(Ad)
+    torch.cuda.synchronize()
+    assert gram_error(K.cpu().numpy(), oracle.gram(A[:, :C])) <= GRAM_TOL
+    assert torch.equal(K, K.T.contiguous())
+    K2 = rfsf.rfsf_ts_gram(Ad, Ad.clone())                 # two operands: the general path
+    torch.cuda.synchronize()
+    assert gram_error(K2.cpu().numpy(), K.cpu().numpy()) <= 1e-6
