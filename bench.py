@@ -51,6 +51,8 @@ def main() -> int:
     ap.add_argument("--workload", default="small", choices=["tiny", "small", "medium", "long", "large"])
     ap.add_argument("--cpu-rows", type=int, default=-1, help="oracle sample size (-1: per-workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--normalize", action="store_true",
+                    help="add the level-wise normalisation of the features to the step (not part of the default path)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="after the timed steps run one plain device copy of this many MiB (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
@@ -83,9 +85,13 @@ def main() -> int:
     def step():
         rfsf.rfsf_ts_features(dev["X"], dev["W"], dev["hash"], dev["sign"], ls, w.D, out=out,
                               workspace=workspace, rff_bf16=w.rff_bf16)
+        if args.normalize:
+            rfsf.rfsf_ts_normalize_features(out, w.M, w.D)
         if X2 is not None:
             rfsf.rfsf_ts_features(X2, dev["W"], dev["hash"], dev["sign"], ls, w.D, out=out2,
                                   workspace=workspace, rff_bf16=w.rff_bf16)
+            if args.normalize:
+                rfsf.rfsf_ts_normalize_features(out2, w.M, w.D)
             rfsf.rfsf_ts_gram(out, out2, K=K)
         else:
             rfsf.rfsf_ts_gram(out, K=K)
@@ -139,6 +145,7 @@ def main() -> int:
     # only the tiles on or above the diagonal (counted here as N(N+1)/2 inner products)
     gram_pairs = w.N * Ny if (w.N2 or ((w.N + 63) // 64) * ((w.N + 63) // 64 + 1) // 2 < 512) else w.N * (w.N + 1) / 2
     entry("gram", "mfma", 2.0 * gram_pairs * w.ncols, "TFLOP/s", MFMA_FP32_PEAK_TFLOPS)
+    entry("normalize", "hbm", 2.0 * 4.0 * n_seq * w.ncols, "GB/s", HBM_PEAK_GBS)
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     roofline = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
     roofline["kernel"] = dominant
@@ -158,7 +165,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "N": w.N, "N2": w.N2, "L": w.L, "d": w.d, "M": w.M, "F": w.F, "D": w.D,
                    "lengthscale": ls, "paths": w.kind, "rff_bf16": w.rff_bf16,
-                   "step": "features + Gram", "workspace_bytes": rec_bytes},
+                   "step": "features + normalisation + Gram" if args.normalize else "features + Gram",
+                   "workspace_bytes": rec_bytes},
         "roofline": roofline,
         "kernels": kernels,
     }
@@ -173,12 +181,14 @@ def main() -> int:
         Wo = wl.round_to_bf16(inp["W"]) if w.rff_bf16 else inp["W"]   # the rounding the bf16 variant applies
         t0 = time.perf_counter()
         want = oracle.features(Xs, Wo, inp["hash"], inp["sign"], ls, w.D)
+        if args.normalize:
+            want = oracle.normalize(want, w.M, w.D)
         t_feat = time.perf_counter() - t0
         t0 = time.perf_counter()
         Kw = oracle.gram(want)
         t_gram = time.perf_counter() - t0
         got = out.cpu().numpy()[sel]
-        err = block_errors(got, want, w.M, w.D)
+        err = block_errors(got, want, w.M, w.D, level0=(1.0 / (w.M + 1) ** 0.5) if args.normalize else 1.0)
         Ksel = (rfsf.rfsf_ts_gram(out[torch.from_numpy(sel).cuda()].contiguous()) if X2 is not None
                 else K[torch.from_numpy(sel).cuda()][:, torch.from_numpy(sel).cuda()])
         torch.cuda.synchronize()

@@ -125,6 +125,19 @@ int rfsf_ts_gram(const float *PhiX, int64_t Nx, int64_t ldx,
                  void *hip_stream);
 
 /*
+ * Level-wise normalisation of feature rows, in place (appendix, class SignatureBase: every
+ * signature level is divided by its own norm and the M+1 levels are averaged, so that the
+ * normalised kernel 1/(M+1) sum_m k_m(x,y) / sqrt(k_m(x,x) k_m(y,y)) is the plain inner product
+ * of the normalised rows and has a unit diagonal):
+ *   Phi[n, 0]                 <- Phi[n, 0] / sqrt(M+1)
+ *   Phi[n, 1+(m-1)D .. mD]    <- the same block / (its Euclidean norm * sqrt(M+1))
+ * A block that is exactly zero (more levels than increments) stays zero.
+ *   Phi [N, ld] float32, ld >= 1 + M*D; columns beyond 1 + M*D are untouched. D need not be a
+ * power of two here. N = 0 is a no-op.
+ */
+int rfsf_ts_normalize_features(float *Phi, int64_t N, int64_t ld, int32_t M, int32_t D, void *hip_stream);
+
+/*
  * Optional per-kernel timing for benchmarks (not part of the method). While enabled, every
  * kernel the library launches is bracketed by HIP events on the stream it is launched on.
  * rfsf_ts_profile_read waits for those events, adds up the elapsed device time per kernel
@@ -134,7 +147,8 @@ int rfsf_ts_gram(const float *PhiX, int64_t Nx, int64_t ldx,
 typedef struct {
     double  ms_rff_increments;   int64_t launches_rff_increments;    /* steps 1-2 kernel */
     double  ms_sketch_fft_scan;  int64_t launches_sketch_fft_scan;   /* steps 3-4 kernel */
-    double  ms_gram;             int64_t launches_gram;              /* Gram kernel      */
+    double  ms_gram;             int64_t launches_gram;              /* Gram kernel(s)   */
+    double  ms_normalize;        int64_t launches_normalize;         /* normalisation    */
 } rfsf_ts_profile;
 
 int rfsf_ts_profile_enable(int on);

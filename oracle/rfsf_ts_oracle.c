@@ -29,6 +29,11 @@
  *      primal features: shape (N, M D + 1); the level-0 term of eq. (ksig finite)
  *      is the constant 1).
  *   6. Gram of features: K[i][j] = <PhiX[i], PhiY[j]> (Sec. 1, P_X P_X^T).
+ *   7. Optional level-wise normalisation (appendix, class SignatureBase: every level divided by
+ *      its own norm, the M+1 levels averaged), as a map on feature rows:
+ *        Phi_m <- Phi_m / (|Phi_m| sqrt(M+1)),  level 0 (the constant 1) <- 1 / sqrt(M+1),
+ *      so that <row_i, row_j> = 1/(M+1) sum_m k_m(i,j) / sqrt(k_m(i,i) k_m(j,j)). A level whose
+ *      block is exactly zero (more levels than increments) stays zero.
  *
  * Inputs are the float32 / int32 arrays the GPU library receives, widened to
  * double on read. OpenMP is used over sequences only (they are independent).
@@ -197,5 +202,27 @@ int rfsf_ts_oracle_gram(const double *PhiX, int64_t Nx, int64_t ldx,
                 acc += PhiX[i * ldx + c] * PhiY[j * ldy + c];
             K[i * ldk + j] = acc;
         }
+    return 0;
+}
+
+/* Step 7, in place on Phi[N][ld] (columns 0 .. M*D). */
+int rfsf_ts_oracle_normalize(double *Phi, int64_t N, int64_t ld, int M, int D)
+{
+    if (N < 0 || M < 1 || D < 1 || ld < 1 + (int64_t)M * D) return -1;
+    const double w = 1.0 / sqrt((double)(M + 1));
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        double *row = Phi + n * ld;
+        row[0] = row[0] * w;                      /* level 0 has norm |1| = 1 */
+        for (int m = 0; m < M; ++m) {
+            double *blk = row + 1 + (int64_t)m * D;
+            double ss = 0.0;
+            for (int j = 0; j < D; ++j) ss += blk[j] * blk[j];
+            if (ss > 0.0) {
+                const double f = w / sqrt(ss);
+                for (int j = 0; j < D; ++j) blk[j] *= f;
+            }
+        }
+    }
     return 0;
 }

@@ -47,6 +47,8 @@ def _load():
         lib.rfsf_ts_oracle_increments.argtypes = [i64, i64, i32, i32, i32, vp, vp, dbl, vp]
         lib.rfsf_ts_oracle_gram.restype = ctypes.c_int
         lib.rfsf_ts_oracle_gram.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, i64]
+        lib.rfsf_ts_oracle_normalize.restype = ctypes.c_int
+        lib.rfsf_ts_oracle_normalize.argtypes = [vp, i64, i64, i32, i32]
         _lib = lib
     return _lib
 
@@ -111,3 +113,14 @@ def gram(PhiX, PhiY=None) -> np.ndarray:
     if rc != 0:
         raise RuntimeError(f"rfsf_ts_oracle_gram failed with code {rc}")
     return K
+
+
+def normalize(Phi, M: int, D: int) -> np.ndarray:
+    """Level-wise normalised copy of feature rows [N, 1 + M*D] (float64)."""
+    out = np.array(Phi, dtype=np.float64, order="C", copy=True)
+    if out.ndim != 2 or out.shape[1] != 1 + M * D:
+        raise ValueError("expected Phi[N, 1 + M*D]")
+    rc = _load().rfsf_ts_oracle_normalize(out.ctypes.data, out.shape[0], out.shape[1], int(M), int(D))
+    if rc != 0:
+        raise RuntimeError(f"rfsf_ts_oracle_normalize failed with code {rc}")
+    return out

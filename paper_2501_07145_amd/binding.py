@@ -33,7 +33,8 @@ class _Shape(ctypes.Structure):
 class _Profile(ctypes.Structure):
     _fields_ = [("ms_rff_increments", ctypes.c_double), ("launches_rff_increments", ctypes.c_int64),
                 ("ms_sketch_fft_scan", ctypes.c_double), ("launches_sketch_fft_scan", ctypes.c_int64),
-                ("ms_gram", ctypes.c_double), ("launches_gram", ctypes.c_int64)]
+                ("ms_gram", ctypes.c_double), ("launches_gram", ctypes.c_int64),
+                ("ms_normalize", ctypes.c_double), ("launches_normalize", ctypes.c_int64)]
 
 
 def lib_path() -> str:
@@ -60,6 +61,8 @@ def load_library():
     lib.rfsf_ts_validate_tables.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.rfsf_ts_gram.restype = ctypes.c_int
     lib.rfsf_ts_gram.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, i64, vp]
+    lib.rfsf_ts_normalize_features.restype = ctypes.c_int
+    lib.rfsf_ts_normalize_features.argtypes = [vp, i64, i64, i32, i32, vp]
     lib.rfsf_ts_profile_enable.restype = ctypes.c_int
     lib.rfsf_ts_profile_enable.argtypes = [ctypes.c_int]
     lib.rfsf_ts_profile_read.restype = ctypes.c_int
@@ -141,6 +144,18 @@ def rfsf_ts_features(X: torch.Tensor, W: torch.Tensor, hash: torch.Tensor, sign:
                                 sign.data_ptr(), float(lengthscale), out.data_ptr(),
                                 workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return out[:, :ncols]
+
+
+def rfsf_ts_normalize_features(Phi: torch.Tensor, M: int, D: int,
+                               stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Level-wise normalisation of feature rows [N, >= 1 + M*D], in place; returns Phi."""
+    if Phi.dim() != 2 or Phi.dtype != torch.float32 or not Phi.is_cuda or Phi.shape[1] < 1 + M * D or \
+            (Phi.shape[1] > 0 and Phi.stride(1) != 1):
+        raise ValueError("Phi must be float32 [N, >= 1+M*D] on the device with unit column stride")
+    N = Phi.shape[0]
+    ld = Phi.stride(0) if N > 1 else max(Phi.stride(0), Phi.shape[1])
+    _check(load_library().rfsf_ts_normalize_features(Phi.data_ptr(), N, ld, int(M), int(D), _stream_ptr(stream)))
+    return Phi
 
 
 def rfsf_ts_validate_tables(hash: torch.Tensor, sign: torch.Tensor, D: int,

@@ -42,13 +42,15 @@ hipError_t launch_fill_trivial(float *out, int64_t n_seq, int64_t ld_out, int64_
 hipError_t launch_gram(const float *PhiX, int64_t Nx, int64_t ldx, const float *PhiY, int64_t Ny,
                        int64_t ldy, int64_t ncols, float *K, int64_t ldk, hipStream_t stream);
 
+hipError_t launch_normalize(float *Phi, int64_t N, int64_t ld, int M, int D, hipStream_t stream);
+
 hipError_t launch_validate_tables(const int32_t *hash, const float *sign, int64_t count, int D,
                                   int *flag, hipStream_t stream);
 
 
 // Per-kernel event timing (see rfsf_ts_profile_enable). A Scope records a start event when
 // constructed and a stop event when destroyed, if profiling is on.
-enum KernelClass { kRffIncrements = 0, kSketchFftScan = 1, kGram = 2, kNumKernelClasses = 3 };
+enum KernelClass { kRffIncrements = 0, kSketchFftScan = 1, kGram = 2, kNormalize = 3, kNumKernelClasses = 4 };
 struct ProfileScope {
     ProfileScope(KernelClass k, hipStream_t stream);
     ~ProfileScope();

@@ -203,6 +203,18 @@ extern "C" int rfsf_ts_gram(const float *PhiX, int64_t Nx, int64_t ldx, const fl
                ? RFSF_OK : RFSF_E_HIP;
 }
 
+extern "C" int rfsf_ts_normalize_features(float *Phi, int64_t N, int64_t ld, int32_t M, int32_t D,
+                                          void *hip_stream)
+{
+    if (N < 0 || M < 1 || D < 1 || N > 0x7fffffffLL) return RFSF_E_BAD_SHAPE;
+    if (ld < 1 + (int64_t)M * D) return RFSF_E_BAD_STRIDE;
+    if (N == 0) return RFSF_OK;
+    if (!Phi) return RFSF_E_NULLPTR;
+    rfsf::ProfileScope scope(rfsf::kNormalize, static_cast<hipStream_t>(hip_stream));
+    return rfsf::launch_normalize(Phi, N, ld, M, D, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? RFSF_OK : RFSF_E_HIP;
+}
+
 extern "C" int rfsf_ts_profile_enable(int on)
 {
     rfsf::g_profile_on = on != 0;
@@ -212,7 +224,7 @@ extern "C" int rfsf_ts_profile_enable(int on)
 extern "C" int rfsf_ts_profile_read(rfsf_ts_profile *out, int reset)
 {
     if (!out) return RFSF_E_NULLPTR;
-    *out = rfsf_ts_profile{0.0, 0, 0.0, 0, 0.0, 0};
+    *out = rfsf_ts_profile{0.0, 0, 0.0, 0, 0.0, 0, 0.0, 0};
     int rc = RFSF_OK;
     for (const rfsf::TimedLaunch &t : rfsf::g_launches) {
         float ms = 0.f;
@@ -223,7 +235,8 @@ extern "C" int rfsf_ts_profile_read(rfsf_ts_profile *out, int reset)
         switch (t.k) {
             case rfsf::kRffIncrements: out->ms_rff_increments += ms; ++out->launches_rff_increments; break;
             case rfsf::kSketchFftScan: out->ms_sketch_fft_scan += ms; ++out->launches_sketch_fft_scan; break;
-            default: out->ms_gram += ms; ++out->launches_gram; break;
+            case rfsf::kGram: out->ms_gram += ms; ++out->launches_gram; break;
+            default: out->ms_normalize += ms; ++out->launches_normalize; break;
         }
     }
     if (reset) {

@@ -8,17 +8,20 @@ BF16_BLOCK_TOL = 2e-2      # the same for the bf16-input projection, against the
 GRAM_TOL = 1e-4            # max |K_gpu - K_oracle| / max |K_oracle|
 
 
-def block_errors(got: np.ndarray, want: np.ndarray, M: int, D: int) -> np.ndarray:
+def block_errors(got: np.ndarray, want: np.ndarray, M: int, D: int, level0: float = 1.0) -> np.ndarray:
     """err[m] = max over sequences of |got_block - want_block|_inf / |want_block|_inf, where a
     block is one level of one sequence (D numbers). Blocks that are exactly zero in the oracle
     (levels above the number of increments) must be exactly zero in `got` (error inf otherwise).
-    Column 0 (level 0) must be exactly 1."""
+    Column 0 (level 0) must be exactly 1 (or within 1e-6 of `level0` for normalised rows)."""
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape == (want.shape[0], 1 + M * D), (got.shape, want.shape)
     if want.shape[0] == 0:
         return np.zeros(M)
-    assert np.all(got[:, 0] == 1.0), "level-0 column must be exactly 1"
+    if level0 == 1.0:
+        assert np.all(got[:, 0] == 1.0), "level-0 column must be exactly 1"
+    else:
+        assert np.all(np.abs(got[:, 0] - level0) <= 1e-6 * abs(level0)), "level-0 column is off"
     g = got[:, 1:].reshape(-1, M, D)
     w = want[:, 1:].reshape(-1, M, D)
     num = np.abs(g - w).max(axis=2)

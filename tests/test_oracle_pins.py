@@ -258,3 +258,36 @@ def test_rejects_bad_arguments(oracle):
         oracle.features(X, W, bad, sign, ls, 4)
     with pytest.raises(RuntimeError):
         oracle.features(X, W, hash_, sign, 0.0, 4)
+
+
+# ---------------------------------------------------------------- level-wise normalisation
+def test_normalisation_matches_the_kernel_level_formula(oracle):
+    """Appendix, class SignatureBase: the normalised kernel is 1/(M+1) sum_m k_m(x,y) /
+    sqrt(k_m(x,x) k_m(y,y)). Evaluated here from the Grams of the unnormalised level blocks and
+    compared with the Gram of the normalised feature rows."""
+    M, D = 3, 16
+    X, W, hash_, sign, ls = _case(30, N=6, L=9, d=2, M=M, F=8, D=D)
+    P = oracle.features(X, W, hash_, sign, ls, D)
+    Pn = oracle.normalize(P, M, D)
+    blocks = P[:, 1:].reshape(6, M, D)
+    Km = np.einsum("imd,jmd->mij", blocks, blocks)                  # per-level Grams
+    dg = np.sqrt(np.einsum("mii->mi", Km))
+    want = (1.0 + (Km / (dg[:, :, None] * dg[:, None, :])).sum(axis=0)) / (M + 1)
+    np.testing.assert_allclose(oracle.gram(Pn), want, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(np.diag(oracle.gram(Pn)), 1.0, rtol=1e-13)
+
+
+def test_normalisation_special_cases(oracle):
+    M, D = 4, 8
+    X, W, hash_, sign, ls = _case(31, N=3, L=3, d=2, M=M, F=4, D=D)   # two increments: levels 3, 4 vanish
+    P = oracle.features(X, W, hash_, sign, ls, D)
+    Pn = oracle.normalize(P, M, D)
+    assert np.all(Pn[:, 1 + 2 * D:] == 0.0)
+    np.testing.assert_allclose(np.sum(Pn * Pn, axis=1), 3.0 / (M + 1), rtol=1e-13)   # levels 0, 1, 2
+    # invariant under a positive rescaling of any level block; a second pass leaves the blocks alone
+    Q = P.copy()
+    Q[:, 1:1 + D] *= 7.5
+    np.testing.assert_allclose(oracle.normalize(Q, M, D), Pn, rtol=1e-13, atol=1e-16)
+    again = oracle.normalize(Pn, M, D)          # blocks already have norm 1/sqrt(M+1): unchanged
+    np.testing.assert_allclose(again[:, 1:], Pn[:, 1:], rtol=1e-13, atol=1e-16)
+    np.testing.assert_allclose(again[:, 0], 1.0 / (M + 1), rtol=1e-14)
