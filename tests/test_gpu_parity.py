@@ -72,6 +72,9 @@ def test_small_64_rows(oracle):
     (2, 40, 3, 8, 20, 256),     # eight levels
     (2, 30, 3, 9, 12, 64),      # nine levels: generic kernel
     (3, 50, 5, 7, 33, 128),     # seven levels, D = 128
+    (2, 9, 70, 2, 40, 64),      # d above 64: plain vector projection kernel
+    (1, 4, 2, 1, 4100, 64),     # 2F above the 16-bit table offsets: generic sketch kernel
+    (2, 12, 3, 2, 600, 256),    # 2F much larger than D: staging area beyond the transform length
 ])
 def test_ragged_shapes(oracle, N, L, d, M, F, D):
     inp = _random_case(100 + N + L + D, N, L, d, M, F, D)
