@@ -72,6 +72,29 @@ int64_t chunk_for(const rfsf_ts_shape *s, size_t bytes)
     return (int64_t)((bytes - fixed) / (incr + state));
 }
 
+// The sketch tables depend only on hash/sign, not on the increments, so they are built on a side
+// stream (default priority) while the first projection kernel runs. The side stream first waits for
+// everything already enqueued on the caller's stream (an earlier call may still be reading the
+// tables), and the caller's stream waits for the tables before the first sketch kernel.
+// Process-wide, created on first use; if anything fails the build simply runs on the caller's stream.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t begin = nullptr, done = nullptr;
+    bool usable = false;
+};
+SideStream &side_stream()
+{
+    static SideStream s;
+    static bool tried = false;
+    if (!tried) {
+        tried = true;
+        s.usable = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
+                   hipEventCreateWithFlags(&s.begin, hipEventDisableTiming) == hipSuccess &&
+                   hipEventCreateWithFlags(&s.done, hipEventDisableTiming) == hipSuccess;
+    }
+    return s;
+}
+
 }  // namespace
 
 extern "C" const char *rfsf_ts_strerror(int code)
@@ -146,8 +169,17 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
     float *dphi = reinterpret_cast<float *>(p_incr);
     float *state = reinterpret_cast<float *>(p_state);
     uint32_t *table = reinterpret_cast<uint32_t *>(p_table);
-    if (rfsf::launch_pack_tables(hash, sign, shape->M, shape->F, shape->D, table, stream) != hipSuccess)
+    SideStream &side = side_stream();
+    bool tables_on_side = false;
+    if (side.usable && hipEventRecord(side.begin, stream) == hipSuccess &&
+        hipStreamWaitEvent(side.stream, side.begin, 0) == hipSuccess) {
+        if (rfsf::launch_pack_tables(hash, sign, shape->M, shape->F, shape->D, table, side.stream) != hipSuccess)
+            return RFSF_E_HIP;
+        if (hipEventRecord(side.done, side.stream) != hipSuccess) return RFSF_E_HIP;
+        tables_on_side = true;
+    } else if (rfsf::launch_pack_tables(hash, sign, shape->M, shape->F, shape->D, table, stream) != hipSuccess) {
         return RFSF_E_HIP;
+    }
 
     const float inv_ls = 1.0f / lengthscale;
     for (int64_t n0 = 0; n0 < shape->N; n0 += chunk) {
@@ -157,6 +189,10 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
             if (rfsf::launch_rff_increments(X + n0 * shape->L * shape->d, W, inv_ls, cnt, shape->L, shape->d,
                                             shape->M, shape->F, shape->rff_bf16 != 0, dphi, stream) != hipSuccess)
                 return RFSF_E_HIP;
+        }
+        if (tables_on_side) {           // join: the tables are needed from here on
+            if (hipStreamWaitEvent(stream, side.done, 0) != hipSuccess) return RFSF_E_HIP;
+            tables_on_side = false;
         }
         {
             rfsf::ProfileScope scope(rfsf::kSketchFftScan, stream);
