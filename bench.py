@@ -43,6 +43,89 @@ MEASURED_TRAFFIC_KIB = {
 }
 
 
+VALU_FP32_PEAK_TFLOPS = 157.3    # MI355X fp32 vector, published (needs packed fp32; 78.6 without)
+COS_FLOPS = 18                   # range reduction (5) + two degree-3 polynomials in r^2 (13) of the cosine used
+
+
+def bench_dp1d(args, w, inp, dev, ls) -> int:
+    """Sibling variant RFSF-DP-1D: one fused kernel (projection on the matrix cores, cosine, time
+    difference, per-component recurrence) + the Gram of its features. ALU-bound: nothing but X, W and
+    bias is read and only the features are written."""
+    import numpy as np
+    import torch
+
+    import paper_2501_07145_amd as rfsf
+    from paper_2501_07145_amd import workloads as wl
+
+    bias_h = wl.make_bias(w, 0)
+    bias = torch.from_numpy(bias_h).cuda()
+    ncols = 1 + w.M * w.F
+    out = torch.empty((w.N, (ncols + 3) // 4 * 4), dtype=torch.float32, device="cuda")[:, :ncols]
+    K = torch.empty((w.N, w.N), dtype=torch.float32, device="cuda")
+
+    def step():
+        rfsf.rfsf_dp1d_features(dev["X"], dev["W"], bias, ls, out=out)
+        rfsf.rfsf_ts_gram(out, K=K)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / args.steps
+    rfsf.rfsf_ts_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = rfsf.rfsf_ts_profile_read(reset=True)
+    rfsf.rfsf_ts_profile_enable(False)
+
+    units = w.N * w.L
+    flops_per_unit = w.M * w.F * (2.0 * w.d + COS_FLOPS + 4.0)       # projection, cosine, difference + recurrence
+    ms = prof["ms_dp1d"] / max(1, prof["launches_dp1d"])
+    achieved = units * flops_per_unit / (ms * 1e-3) / 1e12
+    gram_pairs = w.N * w.N if ((w.N + 63) // 64) * ((w.N + 63) // 64 + 1) // 2 < 512 else w.N * (w.N + 1) / 2
+    gms = prof["ms_gram"] / max(1, prof["launches_gram"])
+    kernels = {
+        "dp1d": {"bound": "alu", "achieved": achieved, "peak": VALU_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                 "frac": achieved / VALU_FP32_PEAK_TFLOPS, "traffic": None, "avg_launch_ms": ms,
+                 "ms_per_step": prof["ms_dp1d"] / args.steps,
+                 "cosines_per_s": units * w.M * w.F / (ms * 1e-3)},
+        "gram": {"bound": "mfma", "achieved": 2.0 * gram_pairs * ncols / (gms * 1e-3) / 1e12,
+                 "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                 "frac": 2.0 * gram_pairs * ncols / (gms * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS, "traffic": None,
+                 "avg_launch_ms": gms, "ms_per_step": prof["ms_gram"] / args.steps},
+    }
+    dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    roofline = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
+    roofline["kernel"] = dominant
+    result = {
+        "metric": "rfsf_dp1d_sequence_steps_per_s", "value": units / t_step, "unit": "sequences*steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "variant": "dp1d", "N": w.N, "L": w.L, "d": w.d, "M": w.M, "F": w.F,
+                   "lengthscale": ls, "paths": w.kind, "step": "DP-1D features + Gram"},
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        from tests.parity import block_errors
+        rows = min(w.N, {"tiny": 16, "small": 1000, "medium": 64, "long": 32, "large": 64}[w.name]
+                   if args.cpu_rows < 0 else args.cpu_rows)
+        sel = np.linspace(0, w.N - 1, rows).round().astype(np.int64)
+        t0 = time.perf_counter()
+        want = oracle.dp1d_features(inp["X"][sel], inp["W"], bias_h, ls)
+        t_feat = time.perf_counter() - t0
+        err = block_errors(out.cpu().numpy()[sel], want, w.M, w.F)
+        result["cpu_baseline"] = {"value": rows * w.L / t_feat, "unit": "sequences*steps/s", "cores": oracle.threads(),
+                                  "kind": "oracle", "sample": f"{rows} of {w.N} sequences, features only, {t_feat:.2f} s, fp64"}
+        result["parity"] = {"rows": int(rows), "max_block_err_per_level": [float(e) for e in err]}
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -51,6 +134,9 @@ def main() -> int:
     ap.add_argument("--workload", default="small", choices=["tiny", "small", "medium", "long", "large"])
     ap.add_argument("--cpu-rows", type=int, default=-1, help="oracle sample size (-1: per-workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variant", default="ts", choices=["ts", "dp1d"],
+                    help="ts: the tensor-sketch path (default, the headline metric); dp1d: the sibling RFSF-DP-1D "
+                         "variant (one fused kernel, features [N, 1+M*F]) plus its Gram")
     ap.add_argument("--normalize", action="store_true",
                     help="add the level-wise normalisation of the features to the step (not part of the default path)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -74,6 +160,9 @@ def main() -> int:
     dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items() if isinstance(v, np.ndarray)}
     ls = inp["lengthscale"]
     X2 = torch.from_numpy(wl.make_paths(w.scaled(N=w.N2), 1)).cuda() if w.N2 else None
+
+    if args.variant == "dp1d":
+        return bench_dp1d(args, w, inp, dev, ls)
 
     rec_bytes, _ = rfsf.rfsf_ts_workspace_bytes(w.N, w.L, w.d, w.M, w.F, w.D, w.rff_bf16)
     workspace = torch.empty(rec_bytes, dtype=torch.uint8, device="cuda")

@@ -138,6 +138,22 @@ int rfsf_ts_gram(const float *PhiX, int64_t Nx, int64_t ldx,
 int rfsf_ts_normalize_features(float *Phi, int64_t N, int64_t ld, int32_t M, int32_t D, void *hip_stream);
 
 /*
+ * Sibling variant RFSF-DP-1D (Sec. 3.3, eq. (dp1d), on the one-dimensional random Fourier features
+ * of Sec. 3.1, eq. (rff_1d) with the scale of the appendix class RandomFourierFeatures1D): F
+ * independent size-1 copies, no sketch and no FFT. For each sequence, level m = 1..M, component i < F:
+ *   phi_m(x)[i] = sqrt(2) cos((x . W[m,:,i]) / lengthscale + bias[m,i])
+ *   Phi_m[i]    = F^{-1/2} sum_{k_1 < ... < k_m} prod_j (phi_j(x_{k_j})[i] - phi_j(x_{k_j - 1})[i])
+ * and out[n, 0] = 1, out[n, 1 + (m-1) F + i] = Phi_m[i]  (1 + M*F columns).
+ *   X [N, L, d], W [M, d, F], bias [M, F] (uniform on [0, 2 pi) for an unbiased kernel estimate),
+ *   out [N, ld_out], ld_out >= 1 + M*F; all float32 device pointers. No workspace is needed.
+ * Limits of this build: d <= 64, M <= 16 (RFSF_E_UNSUPPORTED beyond). N = 0 is a no-op; L = 1 gives
+ * (1, 0, ..., 0).
+ */
+int rfsf_dp1d_features(int64_t N, int64_t L, int32_t d, int32_t M, int32_t F,
+                       const float *X, const float *W, const float *bias, float lengthscale,
+                       float *out, int64_t ld_out, void *hip_stream);
+
+/*
  * Optional per-kernel timing for benchmarks (not part of the method). While enabled, every
  * kernel the library launches is bracketed by HIP events on the stream it is launched on.
  * rfsf_ts_profile_read waits for those events, adds up the elapsed device time per kernel
@@ -149,6 +165,7 @@ typedef struct {
     double  ms_sketch_fft_scan;  int64_t launches_sketch_fft_scan;   /* steps 3-4 kernel */
     double  ms_gram;             int64_t launches_gram;              /* Gram kernel(s)   */
     double  ms_normalize;        int64_t launches_normalize;         /* normalisation    */
+    double  ms_dp1d;             int64_t launches_dp1d;              /* RFSF-DP-1D kernel */
 } rfsf_ts_profile;
 
 int rfsf_ts_profile_enable(int on);

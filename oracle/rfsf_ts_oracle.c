@@ -226,3 +226,60 @@ int rfsf_ts_oracle_normalize(double *Phi, int64_t N, int64_t ld, int M, int D)
     }
     return 0;
 }
+
+/*
+ * Sibling variant RFSF-DP-1D (Sec. 3.3, eq. (dp1d); static map of Sec. 3.1, eq. (rff_1d), with the
+ * appendix scale of class RandomFourierFeatures1D; appendix class DiagonalProjection with
+ * internal size 1): F independent copies of a size-1 one-dimensional random Fourier signature
+ * feature map, per level m = 1..M and component i < F
+ *     phi_m(x)[i]   = sqrt(2) cos( (x . W_m[:, i]) / lengthscale + bias_m[i] )
+ *     u_m[k][i]     = phi_m(x_k)[i] - phi_m(x_{k-1})[i]
+ *     Phi_m[i]      = F^{-1/2} sum_{k_1 < ... < k_m} u_1[k_1][i] ... u_m[k_m][i]
+ * evaluated with the recursion of eq. (rfsf_rec), p = 1, component by component:
+ *     A_m <- A_m + A_{m-1}(before this step) * u_m[k],  A_0 = 1.
+ * out[N][ld_out]: column 0 is 1, columns 1 + (m-1) F + i hold Phi_m[i].
+ */
+int rfsf_dp1d_oracle_features(int64_t N, int64_t L, int d, int M, int F,
+                              const float *X, const float *W, const float *bias,
+                              double lengthscale, double *out, int64_t ld_out)
+{
+    if (N < 0 || L < 1 || d < 1 || M < 1 || F < 1) return -1;
+    if (!(lengthscale > 0.0) || ld_out < 1 + (int64_t)M * F) return -1;
+    const double root2 = sqrt(2.0), scale = 1.0 / sqrt((double)F);
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t n = 0; n < N; ++n) {
+        double *row = out + n * ld_out;
+        double *A = (double *)calloc((size_t)M * F, sizeof(double));
+        double *prev = (double *)malloc(sizeof(double) * (size_t)M * F);
+        double *cur = (double *)malloc(sizeof(double) * (size_t)M * F);
+        if (!A || !prev || !cur) {
+#pragma omp atomic write
+            fail = 1;
+            free(A); free(prev); free(cur);
+            continue;
+        }
+        const float *x = X + n * L * d;
+        for (int64_t t = 0; t < L; ++t) {
+            for (int m = 0; m < M; ++m)
+                for (int i = 0; i < F; ++i) {
+                    double dot = 0.0;
+                    for (int c = 0; c < d; ++c)
+                        dot += (double)x[t * d + c] * (double)W[((int64_t)m * d + c) * F + i];
+                    cur[m * F + i] = root2 * cos(dot / lengthscale + (double)bias[m * F + i]);
+                }
+            if (t > 0) {
+                for (int m = M - 1; m >= 0; --m)          /* descending: A_{m-1} is still the old value */
+                    for (int i = 0; i < F; ++i) {
+                        const double u = cur[m * F + i] - prev[m * F + i];
+                        A[m * F + i] += (m == 0 ? 1.0 : A[(m - 1) * F + i]) * u;
+                    }
+            }
+            double *tmp = prev; prev = cur; cur = tmp;
+        }
+        row[0] = 1.0;
+        for (int64_t j = 0; j < (int64_t)M * F; ++j) row[1 + j] = scale * A[j];
+        free(A); free(prev); free(cur);
+    }
+    return fail ? -2 : 0;
+}

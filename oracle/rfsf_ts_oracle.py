@@ -47,6 +47,8 @@ def _load():
         lib.rfsf_ts_oracle_increments.argtypes = [i64, i64, i32, i32, i32, vp, vp, dbl, vp]
         lib.rfsf_ts_oracle_gram.restype = ctypes.c_int
         lib.rfsf_ts_oracle_gram.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, i64]
+        lib.rfsf_dp1d_oracle_features.restype = ctypes.c_int
+        lib.rfsf_dp1d_oracle_features.argtypes = [i64, i64, i32, i32, i32, vp, vp, vp, dbl, vp, i64]
         lib.rfsf_ts_oracle_normalize.restype = ctypes.c_int
         lib.rfsf_ts_oracle_normalize.argtypes = [vp, i64, i64, i32, i32]
         _lib = lib
@@ -123,4 +125,21 @@ def normalize(Phi, M: int, D: int) -> np.ndarray:
     rc = _load().rfsf_ts_oracle_normalize(out.ctypes.data, out.shape[0], out.shape[1], int(M), int(D))
     if rc != 0:
         raise RuntimeError(f"rfsf_ts_oracle_normalize failed with code {rc}")
+    return out
+
+
+def dp1d_features(X, W, bias, lengthscale: float) -> np.ndarray:
+    """RFSF-DP-1D features, float64 [N, 1 + M*F]: X[N,L,d], W[M,d,F], bias[M,F]."""
+    X, W, bias = _f32(X), _f32(W), _f32(bias)
+    if X.ndim != 3 or W.ndim != 3 or bias.ndim != 2:
+        raise ValueError("expected X[N,L,d], W[M,d,F], bias[M,F]")
+    N, L, d = X.shape
+    M, d2, F = W.shape
+    if d2 != d or bias.shape != (M, F):
+        raise ValueError("inconsistent shapes")
+    out = np.empty((N, 1 + M * F), dtype=np.float64)
+    rc = _load().rfsf_dp1d_oracle_features(N, L, d, M, F, X.ctypes.data, W.ctypes.data, bias.ctypes.data,
+                                           float(lengthscale), out.ctypes.data, out.shape[1])
+    if rc != 0:
+        raise RuntimeError(f"rfsf_dp1d_oracle_features failed with code {rc}")
     return out

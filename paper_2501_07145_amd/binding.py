@@ -34,7 +34,8 @@ class _Profile(ctypes.Structure):
     _fields_ = [("ms_rff_increments", ctypes.c_double), ("launches_rff_increments", ctypes.c_int64),
                 ("ms_sketch_fft_scan", ctypes.c_double), ("launches_sketch_fft_scan", ctypes.c_int64),
                 ("ms_gram", ctypes.c_double), ("launches_gram", ctypes.c_int64),
-                ("ms_normalize", ctypes.c_double), ("launches_normalize", ctypes.c_int64)]
+                ("ms_normalize", ctypes.c_double), ("launches_normalize", ctypes.c_int64),
+                ("ms_dp1d", ctypes.c_double), ("launches_dp1d", ctypes.c_int64)]
 
 
 def lib_path() -> str:
@@ -63,6 +64,8 @@ def load_library():
     lib.rfsf_ts_gram.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, i64, vp]
     lib.rfsf_ts_normalize_features.restype = ctypes.c_int
     lib.rfsf_ts_normalize_features.argtypes = [vp, i64, i64, i32, i32, vp]
+    lib.rfsf_dp1d_features.restype = ctypes.c_int
+    lib.rfsf_dp1d_features.argtypes = [i64, i64, i32, i32, i32, vp, vp, vp, ctypes.c_float, vp, i64, vp]
     lib.rfsf_ts_profile_enable.restype = ctypes.c_int
     lib.rfsf_ts_profile_enable.argtypes = [ctypes.c_int]
     lib.rfsf_ts_profile_read.restype = ctypes.c_int
@@ -156,6 +159,30 @@ def rfsf_ts_normalize_features(Phi: torch.Tensor, M: int, D: int,
     ld = Phi.stride(0) if N > 1 else max(Phi.stride(0), Phi.shape[1])
     _check(load_library().rfsf_ts_normalize_features(Phi.data_ptr(), N, ld, int(M), int(D), _stream_ptr(stream)))
     return Phi
+
+
+def rfsf_dp1d_features(X: torch.Tensor, W: torch.Tensor, bias: torch.Tensor, lengthscale: float,
+                       out: Optional[torch.Tensor] = None,
+                       stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """RFSF-DP-1D features [N, 1 + M*F] of X[N,L,d] with W[M,d,F], bias[M,F]."""
+    X = _dev(X, torch.float32, "X")
+    W = _dev(W, torch.float32, "W")
+    bias = _dev(bias, torch.float32, "bias")
+    if X.dim() != 3 or W.dim() != 3 or bias.dim() != 2 or W.shape[1] != X.shape[2] or \
+            tuple(bias.shape) != (W.shape[0], W.shape[2]):
+        raise ValueError("expected X[N,L,d], W[M,d,F], bias[M,F]")
+    N, L, d = X.shape
+    M, _, F = W.shape
+    ncols = 1 + M * F
+    if out is None:
+        out = torch.empty((N, (ncols + 3) // 4 * 4), dtype=torch.float32, device=X.device)[:, :ncols]
+    if out.dim() != 2 or out.dtype != torch.float32 or not out.is_cuda or out.shape[0] != N or \
+            out.shape[1] < ncols or (out.shape[1] > 0 and out.stride(1) != 1):
+        raise ValueError("out must be float32 [N, >= 1+M*F] on the device with unit column stride")
+    ld_out = out.stride(0) if N > 1 else max(out.stride(0), out.shape[1])
+    _check(load_library().rfsf_dp1d_features(N, L, d, M, F, X.data_ptr(), W.data_ptr(), bias.data_ptr(),
+                                             float(lengthscale), out.data_ptr(), ld_out, _stream_ptr(stream)))
+    return out[:, :ncols]
 
 
 def rfsf_ts_validate_tables(hash: torch.Tensor, sign: torch.Tensor, D: int,

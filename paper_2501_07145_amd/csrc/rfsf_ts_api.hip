@@ -251,6 +251,23 @@ extern "C" int rfsf_ts_normalize_features(float *Phi, int64_t N, int64_t ld, int
                ? RFSF_OK : RFSF_E_HIP;
 }
 
+extern "C" int rfsf_dp1d_features(int64_t N, int64_t L, int32_t d, int32_t M, int32_t F, const float *X,
+                                  const float *W, const float *bias, float lengthscale, float *out,
+                                  int64_t ld_out, void *hip_stream)
+{
+    if (N < 0 || L < 1 || d < 1 || M < 1 || F < 1 || N > 0x7fffffffLL || L > ((int64_t)1 << 40) || F > (1 << 24))
+        return RFSF_E_BAD_SHAPE;
+    if (ld_out < 1 + (int64_t)M * F) return RFSF_E_BAD_STRIDE;
+    if (!(lengthscale > 0.0f) || !std::isfinite(lengthscale)) return RFSF_E_BAD_LENGTHSCALE;
+    if (d > 64 || M > 16 || (F + 255) / 256 > 65535) return RFSF_E_UNSUPPORTED;
+    if (N == 0) return RFSF_OK;
+    if (!X || !W || !bias || !out) return RFSF_E_NULLPTR;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    rfsf::ProfileScope scope(rfsf::kDp1d, stream);
+    return rfsf::launch_dp1d(X, W, bias, 1.0f / lengthscale, N, L, d, M, F, out, ld_out, stream) == hipSuccess
+               ? RFSF_OK : RFSF_E_HIP;
+}
+
 extern "C" int rfsf_ts_profile_enable(int on)
 {
     rfsf::g_profile_on = on != 0;
@@ -260,7 +277,7 @@ extern "C" int rfsf_ts_profile_enable(int on)
 extern "C" int rfsf_ts_profile_read(rfsf_ts_profile *out, int reset)
 {
     if (!out) return RFSF_E_NULLPTR;
-    *out = rfsf_ts_profile{0.0, 0, 0.0, 0, 0.0, 0, 0.0, 0};
+    *out = rfsf_ts_profile{0.0, 0, 0.0, 0, 0.0, 0, 0.0, 0, 0.0, 0};
     int rc = RFSF_OK;
     for (const rfsf::TimedLaunch &t : rfsf::g_launches) {
         float ms = 0.f;
@@ -272,7 +289,8 @@ extern "C" int rfsf_ts_profile_read(rfsf_ts_profile *out, int reset)
             case rfsf::kRffIncrements: out->ms_rff_increments += ms; ++out->launches_rff_increments; break;
             case rfsf::kSketchFftScan: out->ms_sketch_fft_scan += ms; ++out->launches_sketch_fft_scan; break;
             case rfsf::kGram: out->ms_gram += ms; ++out->launches_gram; break;
-            default: out->ms_normalize += ms; ++out->launches_normalize; break;
+            case rfsf::kNormalize: out->ms_normalize += ms; ++out->launches_normalize; break;
+            default: out->ms_dp1d += ms; ++out->launches_dp1d; break;
         }
     }
     if (reset) {

@@ -128,6 +128,13 @@ def make_tables(w: Workload, seed: int = 0):
     return W, hash_, sign
 
 
+def make_bias(w: Workload, seed: int = 0) -> np.ndarray:
+    """bias[M, F] float32 ~ U[0, 2 pi) for the one-dimensional random Fourier features of the DP-1D
+    variant; its own stream PCG64(SeedSequence([seed, 2])), so the other tables are unchanged."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([int(seed), 2])))
+    return rng.uniform(0.0, 2.0 * math.pi, size=(w.M, w.F)).astype(np.float32)
+
+
 def make_inputs(w: Workload, seed: int = 0):
     """dict with X, W, hash, sign, lengthscale for one batch."""
     W, hash_, sign = make_tables(w, seed)
