@@ -126,6 +126,91 @@ def bench_dp1d(args, w, inp, dev, ls) -> int:
     return 0
 
 
+def bench_trp(args, w, inp, dev, ls) -> int:
+    """Sibling variant RFSF-TRP with Q = D projections per level: projection kernel (as in the main path),
+    one fp32 MFMA GEMM per level [N*L, 2F] x [2F, Q], a streaming scan over time, then the Gram."""
+    import numpy as np
+    import torch
+
+    import paper_2501_07145_amd as rfsf
+    from paper_2501_07145_amd import workloads as wl
+
+    Q = w.D
+    Z_h = wl.make_projections(w, 0)
+    Z = torch.from_numpy(Z_h).cuda()
+    ncols = 1 + w.M * Q
+    rec, _ = rfsf.rfsf_trp_workspace_bytes(w.N, w.L, w.d, w.M, w.F, Q, w.rff_bf16)
+    workspace = torch.empty(rec, dtype=torch.uint8, device="cuda")
+    out = torch.empty((w.N, (ncols + 3) // 4 * 4), dtype=torch.float32, device="cuda")[:, :ncols]
+    K = torch.empty((w.N, w.N), dtype=torch.float32, device="cuda")
+
+    def step():
+        rfsf.rfsf_trp_features(dev["X"], dev["W"], Z, ls, out=out, workspace=workspace, rff_bf16=w.rff_bf16)
+        rfsf.rfsf_ts_gram(out, K=K)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / args.steps
+    rfsf.rfsf_ts_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = rfsf.rfsf_ts_profile_read(reset=True)
+    rfsf.rfsf_ts_profile_enable(False)
+
+    units = w.N * w.L
+    kernels = {}
+
+    def entry(name, bound, work_per_step, unit, peak):
+        n = prof[f"launches_{name}"]
+        if n == 0:
+            return
+        avg_ms = prof[f"ms_{name}"] / n
+        achieved = work_per_step * args.steps / n / (avg_ms * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+        kernels[name] = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+                         "traffic": None, "avg_launch_ms": avg_ms, "launches_per_step": n / args.steps,
+                         "ms_per_step": prof[f"ms_{name}"] / args.steps}
+
+    entry("rff_increments", "hbm", units * (4.0 * w.d + 4.0 * w.M * 2 * w.F), "GB/s", HBM_PEAK_GBS)
+    entry("trp_project", "mfma", 2.0 * units * w.M * 2 * w.F * Q, "TFLOP/s", MFMA_FP32_PEAK_TFLOPS)   # M GEMMs per scope
+    entry("trp_scan", "hbm", 4.0 * units * w.M * Q + 4.0 * w.N * ncols, "GB/s", HBM_PEAK_GBS)
+    gram_pairs = w.N * w.N if ((w.N + 63) // 64) * ((w.N + 63) // 64 + 1) // 2 < 512 else w.N * (w.N + 1) / 2
+    entry("gram", "mfma", 2.0 * gram_pairs * ncols, "TFLOP/s", MFMA_FP32_PEAK_TFLOPS)
+    dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    roofline = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
+    roofline["kernel"] = dominant
+    result = {
+        "metric": "rfsf_trp_sequence_steps_per_s", "value": units / t_step, "unit": "sequences*steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16+f32" if w.rff_bf16 else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "variant": "trp", "N": w.N, "L": w.L, "d": w.d, "M": w.M, "F": w.F, "Q": Q,
+                   "lengthscale": ls, "paths": w.kind, "step": "TRP features + Gram", "workspace_bytes": rec},
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        from tests.parity import block_errors
+        rows = min(w.N, {"tiny": 16, "small": 200, "medium": 16, "long": 8, "large": 8}[w.name]
+                   if args.cpu_rows < 0 else args.cpu_rows)
+        sel = np.linspace(0, w.N - 1, rows).round().astype(np.int64)
+        Wo = wl.round_to_bf16(inp["W"]) if w.rff_bf16 else inp["W"]
+        t0 = time.perf_counter()
+        want = oracle.trp_features(inp["X"][sel], Wo, Z_h, ls)
+        t_feat = time.perf_counter() - t0
+        err = block_errors(out.cpu().numpy()[sel], want, w.M, Q)
+        result["cpu_baseline"] = {"value": rows * w.L / t_feat, "unit": "sequences*steps/s", "cores": oracle.threads(),
+                                  "kind": "oracle", "sample": f"{rows} of {w.N} sequences, features only, {t_feat:.2f} s, fp64"}
+        result["parity"] = {"rows": int(rows), "max_block_err_per_level": [float(e) for e in err]}
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -134,9 +219,10 @@ def main() -> int:
     ap.add_argument("--workload", default="small", choices=["tiny", "small", "medium", "long", "large"])
     ap.add_argument("--cpu-rows", type=int, default=-1, help="oracle sample size (-1: per-workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--variant", default="ts", choices=["ts", "dp1d"],
+    ap.add_argument("--variant", default="ts", choices=["ts", "dp1d", "trp"],
                     help="ts: the tensor-sketch path (default, the headline metric); dp1d: the sibling RFSF-DP-1D "
-                         "variant (one fused kernel, features [N, 1+M*F]) plus its Gram")
+                         "variant (one fused kernel, features [N, 1+M*F]) plus its Gram; trp: the sibling RFSF-TRP variant "
+                         "(Q = D Gaussian projections per level) plus its Gram")
     ap.add_argument("--normalize", action="store_true",
                     help="add the level-wise normalisation of the features to the step (not part of the default path)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -163,6 +249,8 @@ def main() -> int:
 
     if args.variant == "dp1d":
         return bench_dp1d(args, w, inp, dev, ls)
+    if args.variant == "trp":
+        return bench_trp(args, w, inp, dev, ls)
 
     rec_bytes, _ = rfsf.rfsf_ts_workspace_bytes(w.N, w.L, w.d, w.M, w.F, w.D, w.rff_bf16)
     workspace = torch.empty(rec_bytes, dtype=torch.uint8, device="cuda")

@@ -154,6 +154,24 @@ int rfsf_dp1d_features(int64_t N, int64_t L, int32_t d, int32_t M, int32_t F,
                        float *out, int64_t ld_out, void *hip_stream);
 
 /*
+ * Sibling variant RFSF-TRP (Sec. 3.4, eqs. (trp_def), (trp), (trp_rec); appendix class
+ * TensorizedRandomProjection): the feature increments delta_m[k] of rfsf_ts_features (same X, W,
+ * lengthscale, cos-then-sin order) are projected per level by an independent Gaussian matrix and
+ * combined by Hadamard products instead of circular convolutions:
+ *   p_m[k]  = Z[m] delta_m[k]                       Z [M, Q, 2F] float32, i.i.d. N(0,1) draws,
+ *                                                   each projection vector contiguous
+ *   Phi_m   = Q^{-1/2} sum_{k_1 < ... < k_m} p_1[k_1] (.) ... (.) p_m[k_m]
+ * and out[n, 0] = 1, out[n, 1 + (m-1) Q + q] = Phi_m[q]   (1 + M*Q columns).
+ * The shape struct is the one of rfsf_ts_features with D meaning Q (any Q >= 1, no power of two
+ * needed); ld_out >= 1 + M*Q; rff_bf16 is honoured. M <= 16 in this build. The workspace holds the
+ * increments and their projections for one chunk of sequences; sizes from rfsf_trp_workspace_bytes.
+ */
+int rfsf_trp_workspace_bytes(const rfsf_ts_shape *shape, size_t *recommended_bytes, size_t *minimum_bytes);
+int rfsf_trp_features(const rfsf_ts_shape *shape, const float *X, const float *W, const float *Z,
+                      float lengthscale, float *out, void *workspace, size_t workspace_bytes,
+                      void *hip_stream);
+
+/*
  * Optional per-kernel timing for benchmarks (not part of the method). While enabled, every
  * kernel the library launches is bracketed by HIP events on the stream it is launched on.
  * rfsf_ts_profile_read waits for those events, adds up the elapsed device time per kernel
@@ -166,6 +184,8 @@ typedef struct {
     double  ms_gram;             int64_t launches_gram;              /* Gram kernel(s)   */
     double  ms_normalize;        int64_t launches_normalize;         /* normalisation    */
     double  ms_dp1d;             int64_t launches_dp1d;              /* RFSF-DP-1D kernel */
+    double  ms_trp_project;      int64_t launches_trp_project;       /* RFSF-TRP GEMMs   */
+    double  ms_trp_scan;         int64_t launches_trp_scan;          /* RFSF-TRP scan    */
 } rfsf_ts_profile;
 
 int rfsf_ts_profile_enable(int on);

@@ -283,3 +283,55 @@ int rfsf_dp1d_oracle_features(int64_t N, int64_t L, int d, int M, int F,
     }
     return fail ? -2 : 0;
 }
+
+/*
+ * Sibling variant RFSF-TRP (Sec. 3.4, eqs. (trp_def), (trp), (trp_rec) read with kappa for k; appendix
+ * class TensorizedRandomProjection): the random Fourier increments of steps 1-2 above are projected
+ * per level by an independent Gaussian matrix and combined by Hadamard products,
+ *     p_m[k]   = Z_m delta_m[k]                  Z_m [Q x 2F], i.i.d. N(0, 1)
+ *     A_m     <- A_m + A_{m-1}(before this step) (.) p_m[k],   A_0 = 1 (all ones)
+ *     Phi_m    = Q^{-1/2} A_m   =  Q^{-1/2} sum_{k_1<...<k_m} p_1[k_1] (.) ... (.) p_m[k_m].
+ * Z is stored [M][Q][2F] (each projection vector contiguous). out[N][ld_out]: column 0 is 1,
+ * columns 1 + (m-1) Q + q hold Phi_m[q].
+ */
+int rfsf_trp_oracle_features(int64_t N, int64_t L, int d, int M, int F, int Q,
+                             const float *X, const float *W, const float *Z,
+                             double lengthscale, double *out, int64_t ld_out)
+{
+    if (N < 0 || L < 1 || d < 1 || M < 1 || F < 1 || Q < 1) return -1;
+    if (!(lengthscale > 0.0) || ld_out < 1 + (int64_t)M * Q) return -1;
+    const int64_t T = L - 1;
+    const int twoF = 2 * F;
+    const double scale = 1.0 / sqrt((double)Q);
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t n = 0; n < N; ++n) {
+        double *row = out + n * ld_out;
+        row[0] = 1.0;
+        for (int64_t j = 0; j < (int64_t)M * Q; ++j) row[1 + j] = 0.0;
+        if (T == 0) continue;
+        double *delta = (double *)malloc(sizeof(double) * (size_t)M * T * twoF);
+        double *phi = (double *)malloc(sizeof(double) * 2 * twoF);
+        double *A = (double *)calloc((size_t)M * Q, sizeof(double));
+        if (!delta || !phi || !A) {
+#pragma omp atomic write
+            fail = 1;
+            free(delta); free(phi); free(A);
+            continue;
+        }
+        increments_one(L, d, M, F, X + n * L * d, W, lengthscale, delta, phi);
+        for (int64_t k = 0; k < T; ++k)
+            for (int m = M - 1; m >= 0; --m) {            /* descending: A_{m-1} is still the old value */
+                const double *dl = delta + ((int64_t)m * T + k) * twoF;
+                for (int q = 0; q < Q; ++q) {
+                    const float *z = Z + ((int64_t)m * Q + q) * twoF;
+                    double p = 0.0;
+                    for (int a = 0; a < twoF; ++a) p += (double)z[a] * dl[a];
+                    A[m * Q + q] += (m == 0 ? 1.0 : A[(m - 1) * Q + q]) * p;
+                }
+            }
+        for (int64_t j = 0; j < (int64_t)M * Q; ++j) row[1 + j] = scale * A[j];
+        free(delta); free(phi); free(A);
+    }
+    return fail ? -2 : 0;
+}

@@ -49,6 +49,8 @@ def _load():
         lib.rfsf_ts_oracle_gram.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, i64]
         lib.rfsf_dp1d_oracle_features.restype = ctypes.c_int
         lib.rfsf_dp1d_oracle_features.argtypes = [i64, i64, i32, i32, i32, vp, vp, vp, dbl, vp, i64]
+        lib.rfsf_trp_oracle_features.restype = ctypes.c_int
+        lib.rfsf_trp_oracle_features.argtypes = [i64, i64, i32, i32, i32, i32, vp, vp, vp, dbl, vp, i64]
         lib.rfsf_ts_oracle_normalize.restype = ctypes.c_int
         lib.rfsf_ts_oracle_normalize.argtypes = [vp, i64, i64, i32, i32]
         _lib = lib
@@ -142,4 +144,22 @@ def dp1d_features(X, W, bias, lengthscale: float) -> np.ndarray:
                                            float(lengthscale), out.ctypes.data, out.shape[1])
     if rc != 0:
         raise RuntimeError(f"rfsf_dp1d_oracle_features failed with code {rc}")
+    return out
+
+
+def trp_features(X, W, Z, lengthscale: float) -> np.ndarray:
+    """RFSF-TRP features, float64 [N, 1 + M*Q]: X[N,L,d], W[M,d,F], Z[M,Q,2F]."""
+    X, W, Z = _f32(X), _f32(W), _f32(Z)
+    if X.ndim != 3 or W.ndim != 3 or Z.ndim != 3:
+        raise ValueError("expected X[N,L,d], W[M,d,F], Z[M,Q,2F]")
+    N, L, d = X.shape
+    M, d2, F = W.shape
+    if d2 != d or Z.shape[0] != M or Z.shape[2] != 2 * F:
+        raise ValueError("inconsistent shapes")
+    Q = Z.shape[1]
+    out = np.empty((N, 1 + M * Q), dtype=np.float64)
+    rc = _load().rfsf_trp_oracle_features(N, L, d, M, F, Q, X.ctypes.data, W.ctypes.data, Z.ctypes.data,
+                                          float(lengthscale), out.ctypes.data, out.shape[1])
+    if rc != 0:
+        raise RuntimeError(f"rfsf_trp_oracle_features failed with code {rc}")
     return out

@@ -35,7 +35,9 @@ class _Profile(ctypes.Structure):
                 ("ms_sketch_fft_scan", ctypes.c_double), ("launches_sketch_fft_scan", ctypes.c_int64),
                 ("ms_gram", ctypes.c_double), ("launches_gram", ctypes.c_int64),
                 ("ms_normalize", ctypes.c_double), ("launches_normalize", ctypes.c_int64),
-                ("ms_dp1d", ctypes.c_double), ("launches_dp1d", ctypes.c_int64)]
+                ("ms_dp1d", ctypes.c_double), ("launches_dp1d", ctypes.c_int64),
+                ("ms_trp_project", ctypes.c_double), ("launches_trp_project", ctypes.c_int64),
+                ("ms_trp_scan", ctypes.c_double), ("launches_trp_scan", ctypes.c_int64)]
 
 
 def lib_path() -> str:
@@ -66,6 +68,10 @@ def load_library():
     lib.rfsf_ts_normalize_features.argtypes = [vp, i64, i64, i32, i32, vp]
     lib.rfsf_dp1d_features.restype = ctypes.c_int
     lib.rfsf_dp1d_features.argtypes = [i64, i64, i32, i32, i32, vp, vp, vp, ctypes.c_float, vp, i64, vp]
+    lib.rfsf_trp_workspace_bytes.restype = ctypes.c_int
+    lib.rfsf_trp_workspace_bytes.argtypes = [ctypes.POINTER(_Shape), ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    lib.rfsf_trp_features.restype = ctypes.c_int
+    lib.rfsf_trp_features.argtypes = [ctypes.POINTER(_Shape), vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
     lib.rfsf_ts_profile_enable.restype = ctypes.c_int
     lib.rfsf_ts_profile_enable.argtypes = [ctypes.c_int]
     lib.rfsf_ts_profile_read.restype = ctypes.c_int
@@ -182,6 +188,45 @@ def rfsf_dp1d_features(X: torch.Tensor, W: torch.Tensor, bias: torch.Tensor, len
     ld_out = out.stride(0) if N > 1 else max(out.stride(0), out.shape[1])
     _check(load_library().rfsf_dp1d_features(N, L, d, M, F, X.data_ptr(), W.data_ptr(), bias.data_ptr(),
                                              float(lengthscale), out.data_ptr(), ld_out, _stream_ptr(stream)))
+    return out[:, :ncols]
+
+
+def rfsf_trp_workspace_bytes(N: int, L: int, d: int, M: int, F: int, Q: int, rff_bf16: bool = False):
+    """(recommended_bytes, minimum_bytes) of scratch for rfsf_trp_features."""
+    shp = _Shape(N, L, d, M, F, Q, 1 + M * Q, int(bool(rff_bf16)))
+    rec, mn = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(load_library().rfsf_trp_workspace_bytes(ctypes.byref(shp), ctypes.byref(rec), ctypes.byref(mn)))
+    return int(rec.value), int(mn.value)
+
+
+def rfsf_trp_features(X: torch.Tensor, W: torch.Tensor, Z: torch.Tensor, lengthscale: float,
+                      out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                      rff_bf16: bool = False, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """RFSF-TRP features [N, 1 + M*Q] of X[N,L,d] with W[M,d,F] and Gaussian projections Z[M,Q,2F]."""
+    X = _dev(X, torch.float32, "X")
+    W = _dev(W, torch.float32, "W")
+    Z = _dev(Z, torch.float32, "Z")
+    if X.dim() != 3 or W.dim() != 3 or Z.dim() != 3 or W.shape[1] != X.shape[2] or Z.shape[0] != W.shape[0] or \
+            Z.shape[2] != 2 * W.shape[2]:
+        raise ValueError("expected X[N,L,d], W[M,d,F], Z[M,Q,2F]")
+    N, L, d = X.shape
+    M, _, F = W.shape
+    Q = Z.shape[1]
+    ncols = 1 + M * Q
+    if out is None:
+        out = torch.empty((N, (ncols + 3) // 4 * 4), dtype=torch.float32, device=X.device)[:, :ncols]
+    if out.dim() != 2 or out.dtype != torch.float32 or not out.is_cuda or out.shape[0] != N or \
+            out.shape[1] < ncols or (out.shape[1] > 0 and out.stride(1) != 1):
+        raise ValueError("out must be float32 [N, >= 1+M*Q] on the device with unit column stride")
+    ld_out = out.stride(0) if N > 1 else max(out.stride(0), out.shape[1])
+    shp = _Shape(N, L, d, M, F, Q, ld_out, int(bool(rff_bf16)))
+    if workspace is None:
+        rec, _ = rfsf_trp_workspace_bytes(N, L, d, M, F, Q, rff_bf16)
+        workspace = torch.empty(rec, dtype=torch.uint8, device=X.device)
+    workspace = _dev(workspace, torch.uint8, "workspace")
+    _check(load_library().rfsf_trp_features(ctypes.byref(shp), X.data_ptr(), W.data_ptr(), Z.data_ptr(),
+                                            float(lengthscale), out.data_ptr(), workspace.data_ptr(),
+                                            workspace.numel(), _stream_ptr(stream)))
     return out[:, :ncols]
 
 

@@ -46,6 +46,10 @@ hipError_t launch_gram(const float *PhiX, int64_t Nx, int64_t ldx, const float *
 hipError_t launch_dp1d(const float *X, const float *W, const float *bias, float inv_lengthscale, int64_t N,
                        int64_t L, int d, int M, int F, float *out, int64_t ld_out, hipStream_t stream);
 
+// RFSF-TRP second stage: recurrence over time on the projected increments P[n_seq*L][M][Q]; M <= 16.
+hipError_t launch_trp_scan(const float *P, int64_t n_seq, int64_t L, int M, int Q, float *out, int64_t ld_out,
+                           hipStream_t stream);
+
 hipError_t launch_normalize(float *Phi, int64_t N, int64_t ld, int M, int D, hipStream_t stream);
 
 hipError_t launch_validate_tables(const int32_t *hash, const float *sign, int64_t count, int D,
@@ -54,7 +58,7 @@ hipError_t launch_validate_tables(const int32_t *hash, const float *sign, int64_
 
 // Per-kernel event timing (see rfsf_ts_profile_enable). A Scope records a start event when
 // constructed and a stop event when destroyed, if profiling is on.
-enum KernelClass { kRffIncrements = 0, kSketchFftScan = 1, kGram = 2, kNormalize = 3, kDp1d = 4, kNumKernelClasses = 5 };
+enum KernelClass { kRffIncrements = 0, kSketchFftScan = 1, kGram = 2, kNormalize = 3, kDp1d = 4, kTrpProject = 5, kTrpScan = 6, kNumKernelClasses = 7 };
 struct ProfileScope {
     ProfileScope(KernelClass k, hipStream_t stream);
     ~ProfileScope();

@@ -268,6 +268,101 @@ extern "C" int rfsf_dp1d_features(int64_t N, int64_t L, int32_t d, int32_t M, in
                ? RFSF_OK : RFSF_E_HIP;
 }
 
+namespace {
+int check_trp_shape(const rfsf_ts_shape *s)
+{
+    if (!s) return RFSF_E_NULLPTR;
+    if (s->N < 0 || s->L < 1 || s->d < 1 || s->M < 1 || s->F < 1 || s->D < 1) return RFSF_E_BAD_SHAPE;
+    if (s->N > ((int64_t)1 << 40) || s->L >= ((int64_t)1 << 31) || s->d > (1 << 20) || s->F > (1 << 24) ||
+        s->D > (1 << 24))
+        return RFSF_E_BAD_SHAPE;
+    if (s->ld_out < 1 + (int64_t)s->M * s->D) return RFSF_E_BAD_STRIDE;
+    if (s->M > 16 || (int64_t)s->M * 2 * s->F > ((int64_t)1 << 26) || (int64_t)s->M * s->D > ((int64_t)1 << 26) ||
+        (int64_t)s->M * ((s->F + 127) / 128) > 65535 || (s->rff_bf16 != 0 && s->d > 128))
+        return RFSF_E_UNSUPPORTED;
+    return RFSF_OK;
+}
+void trp_per_sequence_bytes(const rfsf_ts_shape *s, size_t *incr, size_t *proj)
+{
+    *incr = (size_t)s->L * (size_t)s->M * 2u * (size_t)s->F * sizeof(float);
+    *proj = (size_t)s->L * (size_t)s->M * (size_t)s->D * sizeof(float);
+}
+constexpr size_t kTrpFixed = 3 * kAlign;
+}  // namespace
+
+extern "C" int rfsf_trp_workspace_bytes(const rfsf_ts_shape *shape, size_t *recommended_bytes,
+                                        size_t *minimum_bytes)
+{
+    const int rc = check_trp_shape(shape);
+    if (rc != RFSF_OK) return rc;
+    size_t incr, proj;
+    trp_per_sequence_bytes(shape, &incr, &proj);
+    const size_t per = incr + proj;
+    int64_t chunk = (int64_t)(kChunkBytesTarget / per);
+    if (chunk < 1) chunk = 1;
+    if (chunk > shape->N) chunk = shape->N > 0 ? shape->N : 1;
+    if (shape->N > 0) {
+        const int64_t nchunks = (shape->N + chunk - 1) / chunk;
+        chunk = (shape->N + nchunks - 1) / nchunks;
+    }
+    if (recommended_bytes) *recommended_bytes = (size_t)chunk * per + kTrpFixed;
+    if (minimum_bytes) *minimum_bytes = per + kTrpFixed;
+    return RFSF_OK;
+}
+
+extern "C" int rfsf_trp_features(const rfsf_ts_shape *shape, const float *X, const float *W, const float *Z,
+                                 float lengthscale, float *out, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream)
+{
+    int rc = check_trp_shape(shape);
+    if (rc != RFSF_OK) return rc;
+    if (!(lengthscale > 0.0f) || !std::isfinite(lengthscale)) return RFSF_E_BAD_LENGTHSCALE;
+    if (shape->N == 0) return RFSF_OK;
+    if (!X || !W || !Z || !out) return RFSF_E_NULLPTR;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int Q = shape->D;
+    if (shape->L == 1)
+        return rfsf::launch_fill_trivial(out, shape->N, shape->ld_out, 1 + (int64_t)shape->M * Q, stream) == hipSuccess
+                   ? RFSF_OK : RFSF_E_HIP;
+    if (!workspace) return RFSF_E_NULLPTR;
+    size_t incr, proj;
+    trp_per_sequence_bytes(shape, &incr, &proj);
+    if (workspace_bytes < incr + proj + kTrpFixed) return RFSF_E_WORKSPACE_TOO_SMALL;
+    int64_t chunk = (int64_t)((workspace_bytes - kTrpFixed) / (incr + proj));
+    if (chunk > shape->N) chunk = shape->N;
+    char *base = static_cast<char *>(workspace);
+    const size_t mis = (size_t)(reinterpret_cast<uintptr_t>(base) % kAlign);
+    float *dphi = reinterpret_cast<float *>(base + (mis ? kAlign - mis : 0));
+    float *P = reinterpret_cast<float *>(reinterpret_cast<char *>(dphi) + align_up((size_t)chunk * incr));
+    const int twoF = 2 * shape->F;
+    const int64_t rf = (int64_t)shape->M * twoF, MQ = (int64_t)shape->M * Q;
+    const float inv_ls = 1.0f / lengthscale;
+    for (int64_t n0 = 0; n0 < shape->N; n0 += chunk) {
+        const int64_t cnt = shape->N - n0 < chunk ? shape->N - n0 : chunk;
+        {
+            rfsf::ProfileScope scope(rfsf::kRffIncrements, stream);
+            if (rfsf::launch_rff_increments(X + n0 * shape->L * shape->d, W, inv_ls, cnt, shape->L, shape->d,
+                                            shape->M, shape->F, shape->rff_bf16 != 0, dphi, stream) != hipSuccess)
+                return RFSF_E_HIP;
+        }
+        {   // P[:, m, :] = dphi[:, m, :] Z_m^T, one GEMM per level (rows whose increment does not exist are
+            // computed too and never read)
+            rfsf::ProfileScope scope(rfsf::kTrpProject, stream);
+            for (int m = 0; m < shape->M; ++m)
+                if (rfsf::launch_gram(dphi + (int64_t)m * twoF, cnt * shape->L, rf, Z + (int64_t)m * Q * twoF, Q, twoF,
+                                      twoF, P + (int64_t)m * Q, MQ, stream) != hipSuccess)
+                    return RFSF_E_HIP;
+        }
+        {
+            rfsf::ProfileScope scope(rfsf::kTrpScan, stream);
+            if (rfsf::launch_trp_scan(P, cnt, shape->L, shape->M, Q, out + n0 * shape->ld_out, shape->ld_out,
+                                      stream) != hipSuccess)
+                return RFSF_E_HIP;
+        }
+    }
+    return RFSF_OK;
+}
+
 extern "C" int rfsf_ts_profile_enable(int on)
 {
     rfsf::g_profile_on = on != 0;
@@ -277,7 +372,7 @@ extern "C" int rfsf_ts_profile_enable(int on)
 extern "C" int rfsf_ts_profile_read(rfsf_ts_profile *out, int reset)
 {
     if (!out) return RFSF_E_NULLPTR;
-    *out = rfsf_ts_profile{0.0, 0, 0.0, 0, 0.0, 0, 0.0, 0, 0.0, 0};
+    *out = rfsf_ts_profile{0.0, 0, 0.0, 0, 0.0, 0, 0.0, 0, 0.0, 0, 0.0, 0, 0.0, 0};
     int rc = RFSF_OK;
     for (const rfsf::TimedLaunch &t : rfsf::g_launches) {
         float ms = 0.f;
@@ -290,7 +385,9 @@ extern "C" int rfsf_ts_profile_read(rfsf_ts_profile *out, int reset)
             case rfsf::kSketchFftScan: out->ms_sketch_fft_scan += ms; ++out->launches_sketch_fft_scan; break;
             case rfsf::kGram: out->ms_gram += ms; ++out->launches_gram; break;
             case rfsf::kNormalize: out->ms_normalize += ms; ++out->launches_normalize; break;
-            default: out->ms_dp1d += ms; ++out->launches_dp1d; break;
+            case rfsf::kDp1d: out->ms_dp1d += ms; ++out->launches_dp1d; break;
+            case rfsf::kTrpProject: out->ms_trp_project += ms; ++out->launches_trp_project; break;
+            default: out->ms_trp_scan += ms; ++out->launches_trp_scan; break;
         }
     }
     if (reset) {

@@ -135,6 +135,13 @@ def make_bias(w: Workload, seed: int = 0) -> np.ndarray:
     return rng.uniform(0.0, 2.0 * math.pi, size=(w.M, w.F)).astype(np.float32)
 
 
+def make_projections(w: Workload, seed: int = 0, Q: Optional[int] = None) -> np.ndarray:
+    """Z[M, Q, 2F] float32 ~ N(0, 1): Gaussian projection vectors of the TRP variant (Q defaults to the
+    workload's D); its own stream PCG64(SeedSequence([seed, 3]))."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([int(seed), 3])))
+    return rng.standard_normal((w.M, w.D if Q is None else Q, 2 * w.F)).astype(np.float32)
+
+
 def make_inputs(w: Workload, seed: int = 0):
     """dict with X, W, hash, sign, lengthscale for one batch."""
     W, hash_, sign = make_tables(w, seed)

@@ -19,7 +19,7 @@ def _declared_functions():
             continue
         text = open(os.path.join(inc, fn)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names += re.findall(r"\b(rfsf_ts_[a-z_0-9]+)\s*\(", text)
+        names += re.findall(r"\b(rfsf_[a-z_0-9]+)\s*\(", text)
     return sorted(set(names))
 
 
@@ -27,7 +27,8 @@ def test_every_declared_symbol_is_exported():
     lib = binding.load_library()
     names = _declared_functions()
     assert {"rfsf_ts_features", "rfsf_ts_gram", "rfsf_ts_workspace_bytes", "rfsf_ts_strerror",
-            "rfsf_ts_validate_tables"} <= set(names)
+            "rfsf_ts_validate_tables", "rfsf_ts_normalize_features", "rfsf_dp1d_features", "rfsf_trp_features",
+            "rfsf_trp_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
