@@ -214,8 +214,8 @@ def bench_trp(args, w, inp, dev, ls) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="small", choices=["tiny", "small", "medium", "long", "large"])
     ap.add_argument("--cpu-rows", type=int, default=-1, help="oracle sample size (-1: per-workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
