@@ -214,8 +214,8 @@ def bench_trp(args, w, inp, dev, ls) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 300 for tiny/small, 20 for medium/long, 5 for large)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default: 50 / 3 / 1)")
     ap.add_argument("--workload", default="small", choices=["tiny", "small", "medium", "long", "large"])
     ap.add_argument("--cpu-rows", type=int, default=-1, help="oracle sample size (-1: per-workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -229,6 +229,10 @@ def main() -> int:
                     help="after the timed steps run one plain device copy of this many MiB (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = {"tiny": 300, "small": 300, "large": 5}.get(args.workload, 20)
+    if args.warmup is None:
+        args.warmup = {"tiny": 50, "small": 50, "large": 1}.get(args.workload, 3)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (sequences are independent; sharding N over "
               "GPUs is design-only). Run with --gpus 1.", file=sys.stderr)
