@@ -216,7 +216,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 300 for tiny/small, 20 for medium/long, 5 for large)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default: 50 / 3 / 1)")
-    ap.add_argument("--workload", default="small", choices=["tiny", "small", "medium", "long", "large"])
+    ap.add_argument("--workload", default="small", choices=["tiny", "small", "medium", "long", "large", "paper"])
     ap.add_argument("--cpu-rows", type=int, default=-1, help="oracle sample size (-1: per-workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variant", default="ts", choices=["ts", "dp1d", "trp"],
@@ -355,7 +355,7 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         from tests.parity import block_errors, gram_error
-        default_rows = {"tiny": 16, "small": 1000, "medium": 32, "long": 16, "large": 32}[w.name]
+        default_rows = {"tiny": 16, "small": 1000, "medium": 32, "long": 16, "large": 32, "paper": 100}[w.name]
         rows = min(w.N, default_rows if args.cpu_rows < 0 else args.cpu_rows)
         sel = np.linspace(0, w.N - 1, rows).round().astype(np.int64)
         Xs = inp["X"][sel]

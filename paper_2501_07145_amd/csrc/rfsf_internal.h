@@ -23,14 +23,16 @@ hipError_t launch_rff_increments(const float *X, const float *W, float inv_lengt
                                  float *dphi, hipStream_t stream);
 
 // Steps 3-4: CountSketch, FFT-domain level recursion over time, inverse transform; writes
+// (D is the transform length, a power of two; Dout <= D the number of buckets per level: equal to D,
+// or smaller when the buckets are no power of two and the convolutions are linear, folded at the end)
 // columns 0 .. M*D of `n_seq` rows of out (already offset to the chunk).
 // `state` is scratch for the generic kernel: n_seq * M * (D/2+1) complex floats.
 // `table` (sketch_fft_scan_table_bytes, filled by launch_pack_tables once per call) feeds the tuned kernel.
 hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
-                                  const uint32_t *table, int64_t n_seq, int64_t L, int M, int F, int D,
+                                  const uint32_t *table, int64_t n_seq, int64_t L, int M, int F, int D, int Dout,
                                   float *out, int64_t ld_out, float *state, hipStream_t stream);
-hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int F, int D, uint32_t *table,
-                              hipStream_t stream);
+hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int F, int D, int Dout,
+                              uint32_t *table, hipStream_t stream);
 bool sketch_fft_scan_is_tuned(int M, int F, int D);
 size_t sketch_fft_scan_table_bytes(int M, int F, int D);   // 0 when the generic kernel runs
 size_t sketch_fft_scan_lds_bytes(int M, int F, int D);

@@ -38,6 +38,20 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 bool is_pow2_in_range(int32_t D) { return D >= 2 && D <= 4096 && (D & (D - 1)) == 0; }
 
+// Length of the FFTs. A power-of-two bucket count is transformed as it is (circular convolution
+// modulo D). Any other D >= 1 takes the next power of two that holds the linear convolution of M
+// sketches of length D without wrap-around, M*(D-1)+1 numbers; the kernels fold the result modulo D
+// at the end. 0 if that exceeds the largest transform.
+int transform_length(int32_t M, int32_t D)
+{
+    if (is_pow2_in_range(D)) return D;
+    if (D < 1 || D > 4096) return 0;
+    const int64_t need = (int64_t)M * (D - 1) + 1;
+    int64_t P = 2;
+    while (P < need) P *= 2;
+    return P <= 4096 ? (int)P : 0;
+}
+
 int check_shape(const rfsf_ts_shape *s)
 {
     if (!s) return RFSF_E_NULLPTR;
@@ -45,7 +59,7 @@ int check_shape(const rfsf_ts_shape *s)
     if (s->N > ((int64_t)1 << 40) || s->L > ((int64_t)1 << 40) || s->d > (1 << 20) || s->M > (1 << 10) ||
         s->F > (1 << 24))
         return RFSF_E_BAD_SHAPE;
-    if (!is_pow2_in_range(s->D)) return RFSF_E_D_NOT_POW2;
+    if (transform_length(s->M, s->D) == 0) return RFSF_E_D_NOT_POW2;
     if (s->ld_out < 1 + (int64_t)s->M * s->D) return RFSF_E_BAD_STRIDE;
     return RFSF_OK;
 }
@@ -54,13 +68,14 @@ int check_shape(const rfsf_ts_shape *s)
 void per_sequence_bytes(const rfsf_ts_shape *s, size_t *incr, size_t *state)
 {
     *incr = (size_t)s->L * (size_t)s->M * 2u * (size_t)s->F * sizeof(float);
-    *state = rfsf::sketch_fft_scan_state_bytes(1, s->M, s->D);
+    *state = rfsf::sketch_fft_scan_state_bytes(1, s->M, transform_length(s->M, s->D));
 }
 
 // Fixed part: packed hash/sign table plus room for aligning the three sections.
 size_t fixed_bytes(const rfsf_ts_shape *s)
 {
-    return align_up(rfsf::sketch_fft_scan_table_bytes(s->M, s->F, s->D)) + kIncrementTail + 3 * kAlign;
+    return align_up(rfsf::sketch_fft_scan_table_bytes(s->M, s->F, transform_length(s->M, s->D))) + kIncrementTail +
+           3 * kAlign;
 }
 
 int64_t chunk_for(const rfsf_ts_shape *s, size_t bytes)
@@ -103,7 +118,7 @@ extern "C" const char *rfsf_ts_strerror(int code)
         case RFSF_OK: return "success";
         case RFSF_E_NULLPTR: return "a required pointer is NULL";
         case RFSF_E_BAD_SHAPE: return "bad shape: need N >= 0, L >= 1, d >= 1, M >= 1, F >= 1 within limits";
-        case RFSF_E_D_NOT_POW2: return "D must be a power of two in [2, 4096]";
+        case RFSF_E_D_NOT_POW2: return "D must be a power of two in [2, 4096], or satisfy M*(D-1)+1 <= 4096";
         case RFSF_E_BAD_STRIDE: return "leading dimension smaller than the row length";
         case RFSF_E_BAD_LENGTHSCALE: return "lengthscale must be finite and > 0";
         case RFSF_E_WORKSPACE_TOO_SMALL: return "workspace smaller than rfsf_ts_workspace_bytes' minimum";
@@ -164,7 +179,8 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
     char *base = static_cast<char *>(workspace);
     const size_t mis = (size_t)(reinterpret_cast<uintptr_t>(base) % kAlign);
     char *p_table = base + (mis ? kAlign - mis : 0);
-    char *p_incr = p_table + align_up(rfsf::sketch_fft_scan_table_bytes(shape->M, shape->F, shape->D));
+    const int P = transform_length(shape->M, shape->D);
+    char *p_incr = p_table + align_up(rfsf::sketch_fft_scan_table_bytes(shape->M, shape->F, P));
     char *p_state = p_incr + align_up((size_t)chunk * incr + kIncrementTail);
     float *dphi = reinterpret_cast<float *>(p_incr);
     float *state = reinterpret_cast<float *>(p_state);
@@ -173,11 +189,11 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
     bool tables_on_side = false;
     if (side.usable && hipEventRecord(side.begin, stream) == hipSuccess &&
         hipStreamWaitEvent(side.stream, side.begin, 0) == hipSuccess) {
-        if (rfsf::launch_pack_tables(hash, sign, shape->M, shape->F, shape->D, table, side.stream) != hipSuccess)
+        if (rfsf::launch_pack_tables(hash, sign, shape->M, shape->F, P, shape->D, table, side.stream) != hipSuccess)
             return RFSF_E_HIP;
         if (hipEventRecord(side.done, side.stream) != hipSuccess) return RFSF_E_HIP;
         tables_on_side = true;
-    } else if (rfsf::launch_pack_tables(hash, sign, shape->M, shape->F, shape->D, table, stream) != hipSuccess) {
+    } else if (rfsf::launch_pack_tables(hash, sign, shape->M, shape->F, P, shape->D, table, stream) != hipSuccess) {
         return RFSF_E_HIP;
     }
 
@@ -196,7 +212,7 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
         }
         {
             rfsf::ProfileScope scope(rfsf::kSketchFftScan, stream);
-            if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, table, cnt, shape->L, shape->M, shape->F, shape->D,
+            if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, table, cnt, shape->L, shape->M, shape->F, P, shape->D,
                                              out + n0 * shape->ld_out, shape->ld_out, state, stream) != hipSuccess)
                 return RFSF_E_HIP;
         }
@@ -209,7 +225,7 @@ extern "C" int rfsf_ts_validate_tables(const int32_t *hash, const float *sign, i
 {
     if (!hash || !sign) return RFSF_E_NULLPTR;
     if (M < 1 || F < 1) return RFSF_E_BAD_SHAPE;
-    if (!is_pow2_in_range(D)) return RFSF_E_D_NOT_POW2;
+    if (D < 1 || D > 4096) return RFSF_E_D_NOT_POW2;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     int *flag = nullptr;
     if (hipMalloc(&flag, sizeof(int)) != hipSuccess) return RFSF_E_HIP;

@@ -49,7 +49,7 @@ __device__ float2 *fft_workgroup(float2 *in, float2 *out, const float2 *tw, int 
 // accumulators in global scratch. Correct everywhere, tuned nowhere.
 __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
     const float *__restrict__ dphi, const int32_t *__restrict__ hash, const float *__restrict__ sign,
-    int64_t L, int M, int F, int D, int log2D, float *__restrict__ out, int64_t ld_out,
+    int64_t L, int M, int F, int D, int log2D, int Dout, float *__restrict__ out, int64_t ld_out,
     float2 *__restrict__ state)
 {
     extern __shared__ float2 sm[];
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
             for (int i = threadIdx.x; i < D; i += blockDim.x) buf0[i] = make_float2(0.f, 0.f);
             __syncthreads();
             for (int a = threadIdx.x; a < twoF; a += blockDim.x) {
-                const int h = hash[m * twoF + a] & (D - 1);
+                const int h = ((hash[m * twoF + a] % Dout) + Dout) % Dout;      // D > Dout: linear, folded at the end
                 const float s = copysignf(1.0f, sign[m * twoF + a]);   // increments arrive halved
                 const float v0 = row0[m * twoF + a];
                 const float v1 = two ? row1[m * twoF + a] : 0.f;
@@ -116,7 +116,11 @@ __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
         }
         __syncthreads();
         const float2 *Z = fft_workgroup(buf0, buf1, tw, D, log2D);
-        for (int j = threadIdx.x; j < D; j += blockDim.x) row[1 + (int64_t)m * D + j] = Z[j].x * invD;
+        for (int j = threadIdx.x; j < Dout; j += blockDim.x) {
+            float acc = 0.f;
+            for (int e = j; e < D; e += Dout) acc += Z[e].x;
+            row[1 + (int64_t)m * Dout + j] = acc * invD;
+        }
         __syncthreads();
     }
 }
@@ -126,7 +130,7 @@ __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
 // go to the gather words, ranks >= 2 become fold entries, ordered by rank and padded so that a
 // round of G entries never mixes two ranks (hence never repeats a bucket).
 __global__ __launch_bounds__(256) void build_tables_kernel(
-    const int32_t *__restrict__ hash, const float *__restrict__ sign, int twoF, int D, int G, int LOADB,
+    const int32_t *__restrict__ hash, const float *__restrict__ sign, int twoF, int D, int Dout, int G, int LOADB,
     int PD, uint32_t *__restrict__ table)
 {
     extern __shared__ __attribute__((aligned(16))) int table_scratch[];
@@ -138,7 +142,7 @@ __global__ __launch_bounds__(256) void build_tables_kernel(
     uint32_t *tab = table + (int64_t)m * tl.words;
     const uint32_t zero_off = (uint32_t)tuned::zero_slot(PD, twoF) * 8u;
 
-    for (int a = tid; a < twoF; a += 256) h[a] = hash[(int64_t)m * twoF + a] & (D - 1);
+    for (int a = tid; a < twoF; a += 256) h[a] = ((hash[(int64_t)m * twoF + a] % Dout) + Dout) % Dout;
     for (int e = tid; e < D; e += 256) { src0[e] = -1; src1[e] = -1; }
     for (int r = tid; r <= twoF; r += 256) cls[r] = 0;
     if (tid == 0) max_rank = 0;
@@ -255,8 +259,8 @@ size_t sketch_fft_scan_table_bytes(int M, int F, int D)
     return sizeof(uint32_t) * (size_t)M * tuned::table_layout(D, g.G, g.LOADB, 2 * F).words;
 }
 
-hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int F, int D, uint32_t *table,
-                              hipStream_t stream)
+hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int F, int D, int Dout,
+                              uint32_t *table, hipStream_t stream)
 {
     TunedGeometry g;
     if (!sketch_fft_scan_is_tuned(M, F, D) || !tuned_geometry(D, &g)) return hipSuccess;   // generic kernel: no table
@@ -271,13 +275,13 @@ hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int
             granted = lds;
         }
     }
-    hipLaunchKernelGGL(build_tables_kernel, dim3((unsigned)M), dim3(256), lds, stream, hash, sign, twoF, D, g.G,
-                       g.LOADB, g.PD, table);
+    hipLaunchKernelGGL(build_tables_kernel, dim3((unsigned)M), dim3(256), lds, stream, hash, sign, twoF, D, Dout,
+                       g.G, g.LOADB, g.PD, table);
     return hipGetLastError();
 }
 
 hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
-                                  const uint32_t *table, int64_t n_seq, int64_t L, int M, int F, int D,
+                                  const uint32_t *table, int64_t n_seq, int64_t L, int M, int F, int D, int Dout,
                                   float *out, int64_t ld_out, float *state, hipStream_t stream)
 {
     if (n_seq == 0) return hipSuccess;
@@ -285,12 +289,12 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
     while ((1 << log2D) < D) ++log2D;
     if (sketch_fft_scan_is_tuned(M, F, D)) {
         switch (log2D) {
-            case 6: return tuned::dispatch_levels_6(M, dphi, table, n_seq, L, F, out, ld_out, stream);
-            case 7: return tuned::dispatch_levels_7(M, dphi, table, n_seq, L, F, out, ld_out, stream);
-            case 8: return tuned::dispatch_levels_8(M, dphi, table, n_seq, L, F, out, ld_out, stream);
-            case 9: return tuned::dispatch_levels_9(M, dphi, table, n_seq, L, F, out, ld_out, stream);
-            case 10: return tuned::dispatch_levels_10(M, dphi, table, n_seq, L, F, out, ld_out, stream);
-            default: return tuned::dispatch_levels_11(M, dphi, table, n_seq, L, F, out, ld_out, stream);
+            case 6: return tuned::dispatch_levels_6(M, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
+            case 7: return tuned::dispatch_levels_7(M, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
+            case 8: return tuned::dispatch_levels_8(M, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
+            case 9: return tuned::dispatch_levels_9(M, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
+            case 10: return tuned::dispatch_levels_10(M, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
+            default: return tuned::dispatch_levels_11(M, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
         }
     }
     const size_t lds = sizeof(float2) * (size_t)(2 * D + D / 2 + 2 * (D / 2 + 1));
@@ -302,7 +306,7 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
         lds_granted = lds;
     }
     hipLaunchKernelGGL(sketch_fft_scan_generic, dim3((unsigned)n_seq), dim3(256), lds, stream,
-                       dphi, hash, sign, L, M, F, D, log2D, out, ld_out, reinterpret_cast<float2 *>(state));
+                       dphi, hash, sign, L, M, F, D, log2D, Dout, out, ld_out, reinterpret_cast<float2 *>(state));
     return hipGetLastError();
 }
 

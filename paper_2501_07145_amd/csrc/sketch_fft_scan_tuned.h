@@ -295,7 +295,7 @@ struct WaveFft {
 
 template <int LOG2D, int M>
 __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::LOG2R == 4 ? 4 : 2, 4))) void sketch_fft_scan_kernel(
-    const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L, int F,
+    const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L, int F, int Dout,
     float *__restrict__ out, int64_t ld_out)
 {
     using P = Plan<LOG2D>;
@@ -466,7 +466,14 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
     float *row = out + n * ld_out;
     if (tid == 0) row[0] = 1.0f;
     const float invD = 1.0f / (float)D;
-    for (int j = lane; j < D; j += 64) row[1 + (int64_t)m * D + j] = wave_lds[pad(j)].x * invD;
+    // Dout buckets per level. Dout == D: the transform was circular in D already. Dout < D (a bucket
+    // count that is no power of two): D was chosen so large that the M-fold convolution never wrapped,
+    // and the linear result is folded modulo Dout here.
+    for (int j = lane; j < Dout; j += 64) {
+        float acc = 0.f;
+        for (int e = j; e < D; e += Dout) acc += wave_lds[pad(e)].x;
+        row[1 + (int64_t)m * Dout + j] = acc * invD;
+    }
 }
 
 }  // namespace tuned

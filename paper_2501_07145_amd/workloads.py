@@ -76,6 +76,10 @@ WORKLOADS = {
                      lengthscale=math.sqrt(32.0), kind="ou"),
     "large": Workload("large", N=50000, L=64, d=64, M=5, F=1024, D=2048,
                       lengthscale=8.0, kind="brownian", rff_bf16=True, N2=5000),
+    # shaped like the paper's own scalability runs (Sec. 4: 5-dimensional Brownian motion, M = 5, static
+    # feature and projection sizes 100, batches of 10-100 sequences of length 100 .. 1e5); its bucket
+    # count is no power of two
+    "paper": Workload("paper", N=100, L=1000, d=5, M=5, F=50, D=100, lengthscale=math.sqrt(5.0), kind="brownian"),
 }
 
 

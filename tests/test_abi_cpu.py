@@ -52,7 +52,8 @@ def _shape(**kw):
 
 @pytest.mark.parametrize("kw,code", [
     (dict(N=-1), -2), (dict(L=0), -2), (dict(d=0), -2), (dict(M=0), -2), (dict(F=0), -2),
-    (dict(D=6), -3), (dict(D=1), -3), (dict(D=8192), -3), (dict(D=0), -3), (dict(ld_out=16), -4),
+    (dict(D=3000, ld_out=6001), -3), (dict(D=8192, ld_out=16385), -3), (dict(D=0), -3), (dict(D=-4), -3),
+    (dict(ld_out=16), -4),
 ])
 def test_shape_validation(kw, code):
     lib = binding.load_library()
@@ -81,7 +82,15 @@ def test_argument_validation_without_device_access():
     assert lib.rfsf_ts_gram(None, 4, 9, 256, 4, 9, 9, 256, 4, None) == -1
     assert lib.rfsf_ts_gram(None, 0, 9, None, 4, 9, 9, None, 4, None) == 0
     assert lib.rfsf_ts_validate_tables(None, 256, 2, 4, 8, None) == -1
-    assert lib.rfsf_ts_validate_tables(256, 256, 2, 4, 12, None) == -3
+    assert lib.rfsf_ts_validate_tables(256, 256, 2, 4, 5000, None) == -3
+
+
+def test_bucket_counts_that_are_no_power_of_two_are_accepted_when_small():
+    lib = binding.load_library()
+    rec, mn = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    for D, M, ok in ((6, 2, True), (100, 5, True), (200, 5, True), (1000, 5, False), (1, 3, True), (2049, 2, False)):
+        shp = _shape(D=D, M=M, ld_out=1 + M * D)
+        assert (lib.rfsf_ts_workspace_bytes(ctypes.byref(shp), ctypes.byref(rec), ctypes.byref(mn)) == 0) == ok
 
 
 def test_workspace_sizes():

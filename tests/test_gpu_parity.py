@@ -225,3 +225,20 @@ def test_symmetric_gram_path(oracle, N, C):
     K2 = rfsf.rfsf_ts_gram(Ad, Ad.clone())                 # two operands: the general path
     torch.cuda.synchronize()
     assert gram_error(K2.cpu().numpy(), K.cpu().numpy()) <= 1e-6
+
+
+@pytest.mark.parametrize("N,L,d,M,F,D", [
+    (4, 20, 3, 3, 40, 100),     # the paper's own bucket count: transform length 512
+    (3, 15, 4, 5, 64, 200),     # 1024
+    (3, 12, 2, 2, 8, 6),        # tiny: generic kernel, transform length 16
+    (2, 9, 3, 4, 16, 3),        # D = 3
+    (2, 30, 3, 2, 50, 1000),    # 2048
+    (2, 7, 2, 3, 5, 1),         # a single bucket
+])
+def test_bucket_counts_that_are_no_power_of_two(oracle, N, L, d, M, F, D):
+    """Circular convolution modulo D through a longer power-of-two transform: the M-fold convolution of
+    sketches that occupy [0, D) is linear as long as the transform holds M*(D-1)+1 numbers; the result is
+    folded modulo D at the end."""
+    inp = _random_case(300 + D, N, L, d, M, F, D)
+    _, _, err = _check(inp, D, oracle)
+    print(f"D={D} M={M} block errors", err)
