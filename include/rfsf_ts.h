@@ -51,6 +51,9 @@ typedef struct {
     int64_t ld_out;      /* row stride of `out` in floats, >= 1 + M*D                      */
     int32_t rff_bf16;    /* 0: fp32 projection. 1: W rounded to bf16, X split into two     */
                          /* bf16 terms, products accumulated in fp32 on the matrix cores   */
+    int32_t order;       /* signature order p: 0 or 1 -> strictly increasing time tuples    */
+                         /* (the default); 2 -> a time step may be used twice in a row with  */
+                         /* weight 1/2 (Sec. 2.1, Sec. 3.5 eq. (ts_rec), q = 2). Larger: no. */
 } rfsf_ts_shape;
 
 /* Human-readable text for a return code. Never NULL. Host pointer, static storage. */
@@ -79,6 +82,8 @@ int rfsf_ts_workspace_bytes(const rfsf_ts_shape *shape,
  *   delta_m[k] = phi_m(x_k) - phi_m(x_{k-1})                        k = 1..T
  *   c_m[k][j]  = sum_{a: hash[m,a] = j} sign[m,a] * delta_m[k][a]   j = 0..D-1
  *   Phi_m      = sum_{k_1 < ... < k_m} c_1[k_1] (*) ... (*) c_m[k_m]   (*) circular convolution mod D
+ *                (order 2: sum over k_1 <= ... <= k_m with no index more than twice, each pair of
+ *                equal indices weighted 1/2)
  * and out[n, 0] = 1, out[n, 1 + (m-1) D + j] = Phi_m[j].
  *
  *   X     [N, L, d]  float32, row-major, contiguous

@@ -335,3 +335,90 @@ int rfsf_trp_oracle_features(int64_t N, int64_t L, int d, int M, int F, int Q,
     }
     return fail ? -2 : 0;
 }
+
+/* out[j] = sum_q a[q] * b[(j - q) mod D]: circular convolution, the direct O(D^2) way. */
+static void circular_convolution(int D, const double *a, const double *b, double *out)
+{
+    for (int j = 0; j < D; ++j) {
+        double acc = 0.0;
+        for (int q = 0; q < D; ++q) {
+            int idx = j - q;
+            if (idx < 0) idx += D;
+            acc += a[q] * b[idx];
+        }
+        out[j] = acc;
+    }
+}
+
+/*
+ * RFSF-TS with signature order p >= 1 (Sec. 2.1, the factor 1 / i!^(p); Sec. 3.5, eq. (ts_rec) with the
+ * sum over q = 1..p): a time step may be used up to p times in a row, a run of q equal time indices
+ * weighs 1/q!,
+ *     R_m[k] = sum_{q=1}^{min(p,m)} (1/q!)  P_{m-q}[k] (*) c_{m-q+1}[k] (*) ... (*) c_m[k],
+ *     P_j[k] = sum_{k' < k} R_j[k']  (exclusive prefix over time),  P_0 = unit impulse at bucket 0,
+ *     Phi_m  = sum_k R_m[k].
+ * order = 1 is rfsf_ts_oracle_features (kept as a separate, simpler function). Same arguments otherwise.
+ */
+int rfsf_ts_oracle_features_order(int64_t N, int64_t L, int d, int M, int F, int D, int order,
+                                  const float *X, const float *W,
+                                  const int32_t *hash, const float *sign,
+                                  double lengthscale, double *out, int64_t ld_out)
+{
+    if (N < 0 || L < 1 || d < 1 || M < 1 || F < 1 || D < 1 || order < 1) return -1;
+    if (!(lengthscale > 0.0) || ld_out < 1 + (int64_t)M * D) return -1;
+    const int64_t T = L - 1;
+    const int twoF = 2 * F;
+    for (int64_t i = 0; i < (int64_t)M * twoF; ++i)
+        if (hash[i] < 0 || hash[i] >= D) return -3;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t n = 0; n < N; ++n) {
+        double *row = out + n * ld_out;
+        row[0] = 1.0;
+        for (int64_t j = 0; j < (int64_t)M * D; ++j) row[1 + j] = 0.0;
+        if (T == 0) continue;
+        double *delta = (double *)malloc(sizeof(double) * (size_t)M * T * twoF);
+        double *phi = (double *)malloc(sizeof(double) * 2 * twoF);
+        double *c = (double *)calloc((size_t)M * T * D, sizeof(double));
+        double *P = (double *)calloc((size_t)(M + 1) * D, sizeof(double));   /* P[j]: prefix of level j, j = 0..M */
+        double *R = (double *)malloc(sizeof(double) * (size_t)(M + 1) * D);
+        double *v = (double *)malloc(sizeof(double) * D), *w = (double *)malloc(sizeof(double) * D);
+        if (!delta || !phi || !c || !P || !R || !v || !w) {
+#pragma omp atomic write
+            fail = 1;
+            free(delta); free(phi); free(c); free(P); free(R); free(v); free(w);
+            continue;
+        }
+        increments_one(L, d, M, F, X + n * L * d, W, lengthscale, delta, phi);
+        for (int m = 0; m < M; ++m)
+            for (int64_t k = 0; k < T; ++k) {
+                const double *dl = delta + ((int64_t)m * T + k) * twoF;
+                double *ck = c + ((int64_t)m * T + k) * D;
+                for (int a = 0; a < twoF; ++a)
+                    ck[hash[m * twoF + a]] += (double)sign[m * twoF + a] * dl[a];
+            }
+        P[0] = 1.0;                                     /* level 0: the unit of the convolution */
+        for (int64_t k = 0; k < T; ++k) {
+            for (int m = 1; m <= M; ++m) {              /* R_m[k] from the prefixes before step k */
+                double *Rm = R + (int64_t)m * D;
+                for (int j = 0; j < D; ++j) Rm[j] = 0.0;
+                double fact = 1.0;
+                for (int q = 1; q <= order && q <= m; ++q) {
+                    fact *= (double)q;
+                    memcpy(v, P + (int64_t)(m - q) * D, sizeof(double) * D);
+                    for (int j = m - q + 1; j <= m; ++j) {
+                        circular_convolution(D, v, c + ((int64_t)(j - 1) * T + k) * D, w);
+                        double *t = v; v = w; w = t;
+                    }
+                    for (int j = 0; j < D; ++j) Rm[j] += v[j] / fact;
+                }
+            }
+            for (int m = 1; m <= M; ++m)                /* after use: the prefixes now include step k */
+                for (int j = 0; j < D; ++j) P[(int64_t)m * D + j] += R[(int64_t)m * D + j];
+        }
+        for (int m = 1; m <= M; ++m)
+            for (int j = 0; j < D; ++j) row[1 + (int64_t)(m - 1) * D + j] = P[(int64_t)m * D + j];
+        free(delta); free(phi); free(c); free(P); free(R); free(v); free(w);
+    }
+    return fail ? -2 : 0;
+}

@@ -51,6 +51,8 @@ def _load():
         lib.rfsf_dp1d_oracle_features.argtypes = [i64, i64, i32, i32, i32, vp, vp, vp, dbl, vp, i64]
         lib.rfsf_trp_oracle_features.restype = ctypes.c_int
         lib.rfsf_trp_oracle_features.argtypes = [i64, i64, i32, i32, i32, i32, vp, vp, vp, dbl, vp, i64]
+        lib.rfsf_ts_oracle_features_order.restype = ctypes.c_int
+        lib.rfsf_ts_oracle_features_order.argtypes = [i64, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp, dbl, vp, i64]
         lib.rfsf_ts_oracle_normalize.restype = ctypes.c_int
         lib.rfsf_ts_oracle_normalize.argtypes = [vp, i64, i64, i32, i32]
         _lib = lib
@@ -77,10 +79,17 @@ def _check_inputs(X, W, hash_, sign):
     return X, W, hash_, sign, N, L, d, M, F
 
 
-def features(X, W, hash_, sign, lengthscale: float, D: int) -> np.ndarray:
-    """float64 [N, 1 + M*D]: column 0 is level 0 (= 1), then M blocks of D."""
+def features(X, W, hash_, sign, lengthscale: float, D: int, order: int = 1) -> np.ndarray:
+    """float64 [N, 1 + M*D]: column 0 is level 0 (= 1), then M blocks of D. order = signature order p."""
     X, W, hash_, sign, N, L, d, M, F = _check_inputs(X, W, hash_, sign)
     out = np.empty((N, 1 + M * D), dtype=np.float64)
+    if order != 1:
+        rc = _load().rfsf_ts_oracle_features_order(N, L, d, M, F, int(D), int(order), X.ctypes.data, W.ctypes.data,
+                                                   hash_.ctypes.data, sign.ctypes.data, float(lengthscale),
+                                                   out.ctypes.data, out.shape[1])
+        if rc != 0:
+            raise RuntimeError(f"rfsf_ts_oracle_features_order failed with code {rc}")
+        return out
     rc = _load().rfsf_ts_oracle_features(N, L, d, M, F, int(D), X.ctypes.data, W.ctypes.data,
                                          hash_.ctypes.data, sign.ctypes.data, float(lengthscale),
                                          out.ctypes.data, out.shape[1])
@@ -162,4 +171,16 @@ def trp_features(X, W, Z, lengthscale: float) -> np.ndarray:
                                           float(lengthscale), out.ctypes.data, out.shape[1])
     if rc != 0:
         raise RuntimeError(f"rfsf_trp_oracle_features failed with code {rc}")
+    return out
+
+
+def features_order(X, W, hash_, sign, lengthscale: float, D: int, order: int) -> np.ndarray:
+    """The order-p routine itself (also for order = 1, where it must agree with `features`)."""
+    X, W, hash_, sign, N, L, d, M, F = _check_inputs(X, W, hash_, sign)
+    out = np.empty((N, 1 + M * D), dtype=np.float64)
+    rc = _load().rfsf_ts_oracle_features_order(N, L, d, M, F, int(D), int(order), X.ctypes.data, W.ctypes.data,
+                                               hash_.ctypes.data, sign.ctypes.data, float(lengthscale),
+                                               out.ctypes.data, out.shape[1])
+    if rc != 0:
+        raise RuntimeError(f"rfsf_ts_oracle_features_order failed with code {rc}")
     return out

@@ -27,7 +27,7 @@ class RfsfTsError(RuntimeError):
 class _Shape(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int64), ("L", ctypes.c_int64),
                 ("d", ctypes.c_int32), ("M", ctypes.c_int32), ("F", ctypes.c_int32), ("D", ctypes.c_int32),
-                ("ld_out", ctypes.c_int64), ("rff_bf16", ctypes.c_int32)]
+                ("ld_out", ctypes.c_int64), ("rff_bf16", ctypes.c_int32), ("order", ctypes.c_int32)]
 
 
 class _Profile(ctypes.Structure):
@@ -98,14 +98,14 @@ def _dev(t: torch.Tensor, dtype: torch.dtype, name: str) -> torch.Tensor:
     return t
 
 
-def _shape_of(X, W, hash_, D, ld_out, rff_bf16) -> _Shape:
+def _shape_of(X, W, hash_, D, ld_out, rff_bf16, order=1) -> _Shape:
     if X.dim() != 3 or W.dim() != 3 or hash_.dim() != 2:
         raise ValueError("expected X[N,L,d], W[M,d,F], hash[M,2F]")
     N, L, d = X.shape
     M, d2, F = W.shape
     if d2 != d or tuple(hash_.shape) != (M, 2 * F):
         raise ValueError("inconsistent shapes")
-    return _Shape(N, L, d, M, F, int(D), int(ld_out), int(bool(rff_bf16)))
+    return _Shape(N, L, d, M, F, int(D), int(ld_out), int(bool(rff_bf16)), int(order))
 
 
 def rfsf_ts_workspace_bytes(N: int, L: int, d: int, M: int, F: int, D: int, rff_bf16: bool = False):
@@ -125,7 +125,7 @@ def feature_row_stride(M: int, D: int) -> int:
 def rfsf_ts_features(X: torch.Tensor, W: torch.Tensor, hash: torch.Tensor, sign: torch.Tensor,
                      lengthscale: float, D: int, out: Optional[torch.Tensor] = None,
                      workspace: Optional[torch.Tensor] = None, rff_bf16: bool = False,
-                     stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+                     stream: Optional[torch.cuda.Stream] = None, order: int = 1) -> torch.Tensor:
     """RFSF-TS features of a batch: returns a [N, 1 + M*D] float32 view (row stride
     feature_row_stride(M, D) when allocated here). `out` may be any 2-D float32 device
     tensor with unit column stride and at least 1 + M*D columns; `workspace` any
@@ -144,7 +144,7 @@ def rfsf_ts_features(X: torch.Tensor, W: torch.Tensor, hash: torch.Tensor, sign:
             out.shape[1] < ncols or (out.shape[1] > 0 and out.stride(1) != 1):
         raise ValueError("out must be float32 [N, >= 1+M*D] on the device with unit column stride")
     ld_out = out.stride(0) if N > 1 else max(out.stride(0), out.shape[1])
-    shp = _shape_of(X, W, hash, D, ld_out, rff_bf16)
+    shp = _shape_of(X, W, hash, D, ld_out, rff_bf16, order)
     if workspace is None:
         rec, _ = rfsf_ts_workspace_bytes(shp.N, shp.L, shp.d, shp.M, shp.F, shp.D, rff_bf16)
         workspace = torch.empty(rec, dtype=torch.uint8, device=X.device)

@@ -30,7 +30,7 @@ hipError_t launch_rff_increments(const float *X, const float *W, float inv_lengt
 // `table` (sketch_fft_scan_table_bytes, filled by launch_pack_tables once per call) feeds the tuned kernel.
 hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
                                   const uint32_t *table, int64_t n_seq, int64_t L, int M, int F, int D, int Dout,
-                                  float *out, int64_t ld_out, float *state, hipStream_t stream);
+                                  int order, float *out, int64_t ld_out, float *state, hipStream_t stream);
 hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int F, int D, int Dout,
                               uint32_t *table, hipStream_t stream);
 bool sketch_fft_scan_is_tuned(int M, int F, int D);

@@ -60,6 +60,7 @@ int check_shape(const rfsf_ts_shape *s)
         s->F > (1 << 24))
         return RFSF_E_BAD_SHAPE;
     if (transform_length(s->M, s->D) == 0) return RFSF_E_D_NOT_POW2;
+    if (s->order < 0) return RFSF_E_BAD_SHAPE;
     if (s->ld_out < 1 + (int64_t)s->M * s->D) return RFSF_E_BAD_STRIDE;
     return RFSF_OK;
 }
@@ -168,6 +169,7 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
     }
     if ((int64_t)shape->M * ((shape->F + 127) / 128) > 65535) return RFSF_E_UNSUPPORTED;   // grid limits
     if (shape->rff_bf16 != 0 && shape->d > 128) return RFSF_E_UNSUPPORTED;
+    if (shape->order > 2) return RFSF_E_UNSUPPORTED;
     if ((int64_t)shape->M * 2 * shape->F > ((int64_t)1 << 26)) return RFSF_E_UNSUPPORTED;   // 32-bit row offsets
     if (!workspace) return RFSF_E_NULLPTR;
     int64_t chunk = chunk_for(shape, workspace_bytes);
@@ -213,7 +215,7 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
         {
             rfsf::ProfileScope scope(rfsf::kSketchFftScan, stream);
             if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, table, cnt, shape->L, shape->M, shape->F, P, shape->D,
-                                             out + n0 * shape->ld_out, shape->ld_out, state, stream) != hipSuccess)
+                                             shape->order == 2 ? 2 : 1, out + n0 * shape->ld_out, shape->ld_out, state, stream) != hipSuccess)
                 return RFSF_E_HIP;
         }
     }

@@ -49,13 +49,14 @@ __device__ float2 *fft_workgroup(float2 *in, float2 *out, const float2 *tw, int 
 // accumulators in global scratch. Correct everywhere, tuned nowhere.
 __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
     const float *__restrict__ dphi, const int32_t *__restrict__ hash, const float *__restrict__ sign,
-    int64_t L, int M, int F, int D, int log2D, int Dout, float *__restrict__ out, int64_t ld_out,
+    int64_t L, int M, int F, int D, int log2D, int Dout, int order, float *__restrict__ out, int64_t ld_out,
     float2 *__restrict__ state)
 {
     extern __shared__ float2 sm[];
     const int nb = D / 2 + 1;
     float2 *buf0 = sm, *buf1 = sm + D, *tw = sm + 2 * D;
     float2 *P0 = tw + D / 2, *P1 = P0 + nb;
+    float2 *Q0 = P1 + nb, *Q1 = Q0 + nb, *C0p = Q1 + nb, *C1p = C0p + nb;     // order 2 only (allocated then)
     const int64_t n = blockIdx.x;
     const int64_t T = L - 1;
     const int twoF = 2 * F;
@@ -94,8 +95,23 @@ __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
                 const float2 p0 = m == 0 ? make_float2(1.f, 0.f) : P0[f];
                 const float2 p1 = m == 0 ? make_float2(1.f, 0.f) : P1[f];
                 const float2 a_old = A[m * nb + f];
-                const float2 a_mid = cfma(p0, C0, a_old);
-                const float2 a_new = cfma(p1, C1, a_mid);
+                float2 a_mid = cfma(p0, C0, a_old);
+                float2 a_new;
+                if (order == 2 && m > 0) {      // + 1/2 A_{m-2}(before the step) C_{m-1} C_m
+                    const float2 q0 = m == 1 ? make_float2(1.f, 0.f) : Q0[f];
+                    const float2 q1 = m == 1 ? make_float2(1.f, 0.f) : Q1[f];
+                    a_mid = cfma(make_float2(0.5f * q0.x, 0.5f * q0.y), cmul(C0p[f], C0), a_mid);
+                    a_new = cfma(p1, C1, a_mid);
+                    a_new = cfma(make_float2(0.5f * q1.x, 0.5f * q1.y), cmul(C1p[f], C1), a_new);
+                } else {
+                    a_new = cfma(p1, C1, a_mid);
+                }
+                if (order == 2) {
+                    Q0[f] = p0;
+                    Q1[f] = p1;
+                    C0p[f] = C0;
+                    C1p[f] = C1;
+                }
                 A[m * nb + f] = a_new;
                 P0[f] = a_old;
                 P1[f] = a_mid;
@@ -282,22 +298,23 @@ hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int
 
 hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
                                   const uint32_t *table, int64_t n_seq, int64_t L, int M, int F, int D, int Dout,
-                                  float *out, int64_t ld_out, float *state, hipStream_t stream)
+                                  int order, float *out, int64_t ld_out, float *state, hipStream_t stream)
 {
     if (n_seq == 0) return hipSuccess;
     int log2D = 0;
     while ((1 << log2D) < D) ++log2D;
     if (sketch_fft_scan_is_tuned(M, F, D)) {
         switch (log2D) {
-            case 6: return tuned::dispatch_levels_6(M, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
-            case 7: return tuned::dispatch_levels_7(M, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
-            case 8: return tuned::dispatch_levels_8(M, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
-            case 9: return tuned::dispatch_levels_9(M, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
-            case 10: return tuned::dispatch_levels_10(M, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
-            default: return tuned::dispatch_levels_11(M, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
+            case 6: return tuned::dispatch_levels_6(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
+            case 7: return tuned::dispatch_levels_7(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
+            case 8: return tuned::dispatch_levels_8(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
+            case 9: return tuned::dispatch_levels_9(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
+            case 10: return tuned::dispatch_levels_10(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
+            default: return tuned::dispatch_levels_11(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
         }
     }
-    const size_t lds = sizeof(float2) * (size_t)(2 * D + D / 2 + 2 * (D / 2 + 1));
+    const size_t lds = sizeof(float2) * (size_t)(2 * D + D / 2 + (order == 2 ? 6 : 2) * (D / 2 + 1));
+    if (lds > kLdsPerCu) return hipErrorInvalidValue;     // order 2 with the longest transform
     static size_t lds_granted = 0;        // per process; raising the limit is idempotent
     if (lds > 64 * 1024 && lds > lds_granted) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(sketch_fft_scan_generic),
@@ -306,7 +323,7 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
         lds_granted = lds;
     }
     hipLaunchKernelGGL(sketch_fft_scan_generic, dim3((unsigned)n_seq), dim3(256), lds, stream,
-                       dphi, hash, sign, L, M, F, D, log2D, Dout, out, ld_out, reinterpret_cast<float2 *>(state));
+                       dphi, hash, sign, L, M, F, D, log2D, Dout, order, out, ld_out, reinterpret_cast<float2 *>(state));
     return hipGetLastError();
 }
 

@@ -18,7 +18,8 @@
 //        registers, one LDS exchange per pass, no workgroup barrier inside the transform),
 //   then, after one barrier, every thread owns a few frequency bins, separates the two real
 //   transforms of each slot, and advances the accumulators A_1..A_M of its bins by the two
-//   time steps (A_m += A_{m-1}(before the step) * C_m, A_0 = 1).
+//   time steps (A_m += A_{m-1}(before the step) * C_m, A_0 = 1; with signature order 2 also
+//   + 1/2 A_{m-2}(before the step) * C_{m-1} * C_m, Sec. 3.5 eq. (ts_rec) with q = 2).
 //   After the last time step, wavefront m transforms A_m back and writes block m of the row.
 //   (Fetching the next iteration's rows early was tried: the 32 extra live registers cost more
 //   in occupancy or spills than the hidden latency gains; workgroups of other sequences on the
@@ -293,7 +294,7 @@ struct WaveFft {
     }
 };
 
-template <int LOG2D, int M>
+template <int LOG2D, int M, int ORDER>
 __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::LOG2R == 4 ? 4 : 2, 4))) void sketch_fft_scan_kernel(
     const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L, int F, int Dout,
     float *__restrict__ out, int64_t ld_out)
@@ -422,21 +423,45 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
         // 3. per-bin separation and recurrence, two time steps per slot, levels ascending
 #pragma unroll
         for (int s = 0; s < P::FPW; ++s) {
+            const bool second_step = 2 * (pair0 + s) + 1 < T;      // wavefront-uniform
 #pragma unroll
             for (int b = 0; b < BPT; ++b) {
                 const int f = tid + NT * b;
                 if (f < NB) {
                     const int fi = pad(f), fc = pad((D - f) & (D - 1));
                     float2 p0 = make_float2(1.f, 0.f), p1 = make_float2(1.f, 0.f);
+                    // order 2 (a time step may be used twice in a row, weight 1/2): also the values of
+                    // level l-2 before each step and the transforms of level l-1 at both steps
+                    float2 q0 = make_float2(0.f, 0.f), q1 = q0, c0p = q0, c1p = q0;
 #pragma unroll
                     for (int l = 0; l < M; ++l) {
                         const float2 *Z = lds + ((size_t)l * P::FPW + s) * PS;
                         const float2 z = Z[fi], zc = Z[fc];
                         const float2 C0 = make_float2(z.x + zc.x, z.y - zc.y);
-                        const float2 C1 = make_float2(z.y + zc.y, zc.x - z.x);
+                        // a second step that does not exist (odd number of increments) must contribute
+                        // exactly nothing; the separation alone would leave rounding noise of the first
+                        float2 C1 = make_float2(z.y + zc.y, zc.x - z.x);
+                        if (!second_step) C1 = make_float2(0.f, 0.f);
                         const float2 a_old = A[b][l];
-                        const float2 a_mid = cfmaf(p0, C0, a_old);
-                        A[b][l] = cfmaf(p1, C1, a_mid);
+                        float2 a_mid = cfmaf(p0, C0, a_old);
+                        if constexpr (ORDER == 2) {
+                            if (l > 0) {
+                                const float2 h = cmulf(c0p, C0);
+                                a_mid = cfmaf(make_float2(0.5f * q0.x, 0.5f * q0.y), h, a_mid);
+                            }
+                        }
+                        float2 a_new = cfmaf(p1, C1, a_mid);
+                        if constexpr (ORDER == 2) {
+                            if (l > 0) {
+                                const float2 h = cmulf(c1p, C1);
+                                a_new = cfmaf(make_float2(0.5f * q1.x, 0.5f * q1.y), h, a_new);
+                            }
+                            q0 = p0;
+                            q1 = p1;
+                            c0p = C0;
+                            c1p = C1;
+                        }
+                        A[b][l] = a_new;
                         p0 = a_old;
                         p1 = a_mid;
                     }

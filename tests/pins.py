@@ -109,3 +109,29 @@ def streaming_frequency_domain(delta, hash_, sign, D):
             A[m] += A[m - 1] * Chat[m]
         A[0] += Chat[0]
     return np.stack([np.fft.irfft(A[m], n=D) for m in range(M)])
+
+
+def brute_force_tensor_sketch_order(delta, hash_, sign, D, order):
+    """Phi[M, D] for ONE sequence from the closed definition with signature order p (Sec. 2.1 and Sec. 3.5
+    eq. (ts)): sum over non-decreasing time tuples i_1 <= ... <= i_m in which no time index occurs more
+    than p times, weighted by 1 / prod(multiplicity!), of the sketched explicit tensor product.
+    delta: [T, M, 2F]; pure Python loops, tiny sizes only."""
+    T, M, twoF = delta.shape
+    out = np.zeros((M, D))
+    for m in range(1, M + 1):
+        for idx in itertools.combinations_with_replacement(range(T), m):
+            mult = [len(list(g)) for _, g in itertools.groupby(idx)]
+            if max(mult) > order:
+                continue
+            weight = 1.0
+            for c in mult:
+                weight /= math.factorial(c)
+            for coords in itertools.product(range(twoF), repeat=m):
+                bucket = 0
+                val = weight
+                for k in range(m):
+                    a = coords[k]
+                    bucket += int(hash_[k, a])
+                    val *= float(sign[k, a]) * float(delta[idx[k], k, a])
+                out[m - 1, bucket % D] += val
+    return out

@@ -63,6 +63,8 @@ def test_small_64_rows(oracle):
     (4, 9, 7, 1, 40, 128),      # one level
     (2, 2, 3, 4, 16, 16),       # one increment: levels above 1 vanish
     (2, 3, 3, 4, 16, 16),       # two increments: levels above 2 vanish
+    (3, 2, 3, 4, 32, 64),       # one increment on the tuned kernel: the padded second step adds exactly nothing
+    (2, 4, 5, 5, 64, 1024),     # three increments, five levels
     (7, 65, 19, 6, 70, 64),     # several row tiles with a ragged tail, six levels, D < 2F
     (2, 20, 4, 2, 8, 4096),     # largest D
     (3, 300, 33, 3, 130, 512),  # d above one MFMA K-slab, F with a ragged column tile
@@ -242,3 +244,27 @@ def test_bucket_counts_that_are_no_power_of_two(oracle, N, L, d, M, F, D):
     inp = _random_case(300 + D, N, L, d, M, F, D)
     _, _, err = _check(inp, D, oracle)
     print(f"D={D} M={M} block errors", err)
+
+
+@pytest.mark.parametrize("N,L,d,M,F,D", [
+    (4, 12, 3, 3, 32, 64),      # tuned kernel, several pairs per wavefront
+    (3, 9, 4, 5, 64, 1024),     # one pair per wavefront
+    (2, 8, 3, 4, 16, 16),       # generic kernel
+    (2, 7, 2, 3, 20, 100),      # bucket count that is no power of two
+    (2, 2, 3, 4, 16, 256),      # one increment: level 2 = (1/2) c_1 * c_2, levels 3, 4 vanish
+    (6, 31, 5, 4, 128, 256),    # odd number of increments
+])
+def test_signature_order_two(oracle, N, L, d, M, F, D):
+    """A time step may be used twice in a row, with weight 1/2 (Sec. 2.1; Sec. 3.5 eq. (ts_rec), q = 2)."""
+    inp = _random_case(400 + D + L, N, L, d, M, F, D)
+    got = _gpu_features(inp, D, order=2).cpu().numpy()
+    want = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D, order=2)
+    err = block_errors(got, want, M, D)
+    print(f"order 2, D={D} M={M}: block errors", err)
+    assert np.all(err <= FP32_BLOCK_TOL)
+    one = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D)
+    if L > 2:
+        assert block_errors(got, one, M, D)[1:].max() > 1e-3       # it is not the order-1 map
+    with pytest.raises(binding.RfsfTsError) as e:
+        _gpu_features(inp, D, order=3)
+    assert e.value.code == -9

@@ -291,3 +291,41 @@ def test_normalisation_special_cases(oracle):
     again = oracle.normalize(Pn, M, D)          # blocks already have norm 1/sqrt(M+1): unchanged
     np.testing.assert_allclose(again[:, 1:], Pn[:, 1:], rtol=1e-13, atol=1e-16)
     np.testing.assert_allclose(again[:, 0], 1.0 / (M + 1), rtol=1e-14)
+
+
+# ---------------------------------------------------------------- signature order p > 1
+@pytest.mark.parametrize("T,F,M,D,order", [(5, 1, 3, 4, 2), (4, 2, 3, 8, 2), (4, 1, 4, 4, 3), (3, 2, 3, 4, 3), (5, 1, 2, 2, 2)])
+def test_order_p_bruteforce(oracle, T, F, M, D, order):
+    """Sec. 2.1 (the weights 1 / i!^(p)) and Sec. 3.5 eq. (ts): explicit sum over non-decreasing tuples."""
+    X, W, hash_, sign, ls = _case(40 + T + D + order, N=2, L=T + 1, d=2, M=M, F=F, D=D)
+    got = oracle.features(X, W, hash_, sign, ls, D, order=order)
+    delta = pins.rff_increments_numpy(X, W, ls)
+    for n in range(2):
+        want = pins.brute_force_tensor_sketch_order(delta[n], hash_, sign, D, order)
+        np.testing.assert_allclose(got[n, 1:].reshape(M, D), want, rtol=0, atol=1e-13)
+
+
+def test_order_one_routine_agrees_and_orders_differ(oracle):
+    """The general routine at p = 1 is the strict-tuple oracle; p = 2 changes levels >= 2 only; an order
+    above the number of levels changes nothing more."""
+    X, W, hash_, sign, ls = _case(50, N=3, L=9, d=3, M=4, F=4, D=8)
+    base = oracle.features(X, W, hash_, sign, ls, 8)
+    np.testing.assert_allclose(oracle.features_order(X, W, hash_, sign, ls, 8, 1), base, rtol=0, atol=1e-14)
+    two = oracle.features(X, W, hash_, sign, ls, 8, order=2)
+    np.testing.assert_allclose(two[:, :9], base[:, :9], rtol=0, atol=1e-14)          # levels 0, 1
+    assert np.abs(two[:, 9:] - base[:, 9:]).max() > 1e-6
+    np.testing.assert_allclose(oracle.features(X, W, hash_, sign, ls, 8, order=4),
+                               oracle.features(X, W, hash_, sign, ls, 8, order=7), rtol=0, atol=1e-14)
+
+
+def test_order_p_single_increment(oracle):
+    """One increment (L = 2): only runs of that one time index exist, so level m = (1/m!) c_1 * ... * c_m
+    when m <= p and zero otherwise -- with a constant hash the convolution is a plain product."""
+    X, W, hash_, sign, ls = _case(51, N=2, L=2, d=2, M=3, F=3, D=4)
+    h0 = np.zeros_like(hash_)
+    got = oracle.features(X, W, h0, sign, ls, 4, order=2)[:, 1:].reshape(2, 3, 4)
+    delta = pins.rff_increments_numpy(X, W, ls)[:, 0]                     # [N, M, 2F]
+    u = np.einsum("nma,ma->nm", delta, sign.astype(np.float64))           # bucket-0 sums
+    np.testing.assert_allclose(got[:, 0, 0], u[:, 0], rtol=0, atol=1e-14)
+    np.testing.assert_allclose(got[:, 1, 0], u[:, 0] * u[:, 1] / 2.0, rtol=0, atol=1e-14)
+    assert np.all(got[:, 2] == 0.0) and np.all(got[:, :, 1:] == 0.0)
