@@ -109,7 +109,7 @@ int rfsf_ts_features(const rfsf_ts_shape *shape,
 
 /*
  * Opt-in device pass that checks the table contents: every hash[m,a] in [0, D) and every
- * sign[m,a] equal to +1 or -1. Synchronises `hip_stream` (it has to read the verdict).
+ * sign[m,a] equal to +1 or -1. Synchronises `hip_stream` (it has to read the result).
  * Returns RFSF_OK or RFSF_E_BAD_TABLE.
  */
 int rfsf_ts_validate_tables(const int32_t *hash, const float *sign,

@@ -420,13 +420,19 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
         // 2. FPW transforms per wavefront, in place in the slots
         fft.run_from_registers(my_slot, v);
         __syncthreads();
-        // 3. per-bin separation and recurrence, two time steps per slot, levels ascending
+        // 3. per-bin separation and recurrence, two time steps per slot, levels ascending.
+        // For D = 1024 (128-register budget, one pair per wavefront) the thread index is laundered so that
+        // the LDS addresses of the bins are recomputed here (a few adds) instead of being kept across the
+        // whole iteration as loop invariants, where they were spilled to scratch (measured: 8 % faster
+        // there, slower for the other transform lengths).
+        int tid_here = tid;
+        if constexpr (LOG2D == 10) asm volatile("" : "+v"(tid_here));
 #pragma unroll
         for (int s = 0; s < P::FPW; ++s) {
             const bool second_step = 2 * (pair0 + s) + 1 < T;      // wavefront-uniform
 #pragma unroll
             for (int b = 0; b < BPT; ++b) {
-                const int f = tid + NT * b;
+                const int f = tid_here + NT * b;
                 if (f < NB) {
                     const int fi = pad(f), fc = pad((D - f) & (D - 1));
                     float2 p0 = make_float2(1.f, 0.f), p1 = make_float2(1.f, 0.f);
