@@ -241,11 +241,11 @@ size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D)
 }
 
 namespace {
-struct TunedGeometry { int G, LOADB, PD, FPW, NTWL; };
+struct TunedGeometry { int G /* entries per fold round */, LOADB, PD, FPW, NTWL; };
 bool tuned_geometry(int D, TunedGeometry *g)
 {
     switch (D) {
-#define RFSF_GEOM(L2) case 1 << L2: *g = {tuned::Plan<L2>::G, tuned::Plan<L2>::LOADB, tuned::Plan<L2>::PD, tuned::Plan<L2>::FPW, tuned::Plan<L2>::NTWL}; return true;
+#define RFSF_GEOM(L2) case 1 << L2: *g = {tuned::Plan<L2>::GF, tuned::Plan<L2>::LOADB, tuned::Plan<L2>::PD, tuned::Plan<L2>::FPW, tuned::Plan<L2>::NTWL}; return true;
         RFSF_GEOM(6) RFSF_GEOM(7) RFSF_GEOM(8) RFSF_GEOM(9) RFSF_GEOM(10) RFSF_GEOM(11)
 #undef RFSF_GEOM
         default: return false;

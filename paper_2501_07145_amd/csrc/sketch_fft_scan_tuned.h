@@ -1,7 +1,8 @@
 // Tuned kernel for steps 3-4 (CountSketch, Fourier-domain level recursion over time, inverse
 // transform; Sec. 3.5, eqs. (cs), (ts_def), (ts_rec) with p = 1).
 //
-// Work decomposition (one workgroup per sequence, M wavefronts, wavefront m owns level m):
+// Work decomposition (one workgroup per sequence, M wavefronts, wavefront m owns level m; for D = 2048
+// two wavefronts share a level and its single transform, see Plan::WPL):
 //   per iteration every wavefront handles FPW pairs of consecutive time steps of its level:
 //     1. CountSketch as a gather. The signed increments of the 2*FPW time steps are written to
 //        LDS in their natural order (step 2k -> real part, step 2k+1 -> imaginary part of the
@@ -42,10 +43,12 @@ template <int LOG2D_>
 struct Plan {
     static constexpr int LOG2D = LOG2D_;
     static constexpr int D = 1 << LOG2D;
-    static constexpr int LOG2R = (LOG2D == 11) ? 5 : 4;
+    static constexpr int LOG2R = 4;
     static constexpr int R = 1 << LOG2R;        // points per lane
-    static constexpr int G = D / R;             // lanes per transform
-    static constexpr int FPW = 64 / G;          // transforms per wavefront
+    static constexpr int G = D / R;             // lanes per transform (128 for D = 2048: two wavefronts)
+    static constexpr int WPL = G > 64 ? G / 64 : 1;   // wavefronts per level
+    static constexpr int FPW = G > 64 ? 1 : 64 / G;   // transforms per wavefront (per level when WPL > 1)
+    static constexpr int GF = G > 64 ? 64 : G;  // entries per fold round (the first wavefront of a level folds)
     static constexpr int PD = D + D / 16;       // padded transform length in float2
     static constexpr int LOADB = FPW >= 16 ? 1 : 16 / FPW;   // 64-coordinate groups fetched per batch
     static constexpr int NP = LOG2D <= 4 ? 1 : (LOG2D <= 8 ? 2 : 3);
@@ -64,7 +67,7 @@ struct Plan {
             // half the registers and half the LDS per workgroup doubles the resident workgroups, which
             // outweighs the extra LDS exchange (measured: 20 % faster)
             case 10: return p == 1 ? 4 : 16;
-            default: return p == 1 ? 8 : 16;    // 11
+            default: return p == 1 ? 8 : 16;    // 11: 16 points per lane, two wavefronts per transform
         }
     }
     static constexpr int Ns(int p) { return p == 0 ? 1 : Ns(p - 1) * radix(p - 1); }
@@ -181,6 +184,16 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Exchange point inside a transform: a compiler-level ordering when the transform lives in one
+// wavefront, a workgroup barrier when it spans several (every wavefront of the workgroup runs the same
+// sequence of passes, so the barriers match up).
+template <typename P>
+__device__ __forceinline__ void transform_fence()
+{
+    if constexpr (P::WPL > 1) __syncthreads();
+    else wave_lds_fence();
+}
+
 // Per-lane constants of the wavefront-local FFT.
 template <typename P>
 struct WaveFft {
@@ -263,7 +276,7 @@ struct WaveFft {
     {
         if constexpr (PI < P::NP) {
             constexpr int r = P::radix(PI), Ns = P::Ns(PI), NB = P::R / r, LR = ilog2(r);
-            wave_lds_fence();                    // every lane has its inputs in registers
+            transform_fence<P>();                    // every lane has its inputs in registers
 #pragma unroll
             for (int u = 0; u < NB; ++u) {
                 float2 x[r];
@@ -287,7 +300,7 @@ struct WaveFft {
 #pragma unroll
                 for (int t = 0; t < r; ++t) dst[pad(t * Ns)] = x[bitrev(t, LR)];
             }
-            wave_lds_fence();
+            transform_fence<P>();
             if constexpr (PI + 1 < P::NP) {
 #pragma unroll
                 for (int q = 0; q < P::R; ++q) v[q] = slot[rbase + P::roff(q)];
@@ -298,15 +311,18 @@ struct WaveFft {
 };
 
 template <int LOG2D, int M, int ORDER>
-__global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::LOG2R == 4 ? 4 : 2, 4))) void sketch_fft_scan_kernel(
+__global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
+    __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::WPL == 1 ? 4 : 3, 4))) void sketch_fft_scan_kernel(
     const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L, int F, int Dout,
     float *__restrict__ out, int64_t ld_out)
 {
     using P = Plan<LOG2D>;
-    constexpr int D = P::D, NT = 64 * M, NB = D / 2 + 1, BPT = (NB + NT - 1) / NT;
+    constexpr int D = P::D, NT = 64 * M * P::WPL, NB = D / 2 + 1, BPT = (NB + NT - 1) / NT;
     extern __shared__ float2 lds[];                    // [M][FPW][PS] slots, then the twiddle table
-    const int tid = threadIdx.x, lane = tid & 63, m = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int slot_id = lane / P::G, lg = lane % P::G;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m = wave / P::WPL, sub = wave % P::WPL;        // level, wavefront within the level
+    const int slot_id = P::WPL > 1 ? 0 : lane / P::G;
+    const int lg = P::WPL > 1 ? sub * 64 + lane : lane % P::G; // lane within the transform
     const int twoF = 2 * F;
     const int ZS = zero_slot(P::PD, twoF), PS = slot_stride(P::PD, twoF);
     float2 *twl_table = lds + (size_t)M * P::FPW * PS;          // behind the slots
@@ -316,7 +332,7 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
     const int64_t n = blockIdx.x, T = L - 1;
     const int64_t rf = (int64_t)M * twoF;
     const float *seq = dphi + n * L * rf + (int64_t)m * twoF;   // row k of this level: seq + k * rf
-    const TableLayout tl = table_layout(D, P::G, P::LOADB, twoF);
+    const TableLayout tl = table_layout(D, P::GF, P::LOADB, twoF);
     const uint32_t *tab = table + (int64_t)m * tl.words;
     const int NG = (int)tab[0];
 
@@ -384,19 +400,23 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
 #pragma unroll
         for (int q = 0; q < P::R; ++q) gw[q] = tabi[tl.gather + lg + P::G * q];
 #pragma unroll
-        for (int g = 0; g < kFoldInRegs; ++g) fw[g] = g < NG ? tabi[tl.fold + g * P::G + lg] : kFoldPad << 16;
-        const uint32_t sw0 = tabi[tl.signs + lane];
+        for (int g = 0; g < kFoldInRegs; ++g) fw[g] = g < NG ? tabi[tl.fold + g * P::GF + (lg % P::GF)] : kFoldPad << 16;
+        // a level's wavefronts take the 64*LOADB-coordinate batches in turn
+        const uint32_t sw0 = tabi[tl.signs + sub * 64 + lane];
 
         // 1a. staging, one batch of 64*LOADB coordinates at a time
-        fetch(pair0, 0);
-        stage(0, sw0);
-        for (int bi = 1; bi < tl.nbatch; ++bi) {
+        if (sub < tl.nbatch) {
+            fetch(pair0, sub * 64 * P::LOADB);
+            stage(sub * 64 * P::LOADB, sw0);
+        }
+        for (int bi = sub + P::WPL; bi < tl.nbatch; bi += P::WPL) {
             const int a0 = bi * 64 * P::LOADB;
             fetch(pair0, a0);
             stage(a0, tabi[tl.signs + bi * 64 + lane]);
         }
-        wave_lds_fence();
+        transform_fence<P>();
         // 1b. fold the third and later coordinates of a bucket into its first one, one rank per round
+        // (by the first wavefront of the level when a transform spans several)
         auto fold = [&](uint32_t w) {
             const uint32_t own = w & 0xffffu, tgt = w >> 16;
             if (tgt != kFoldPad) {
@@ -406,10 +426,13 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
             }
             wave_lds_fence();
         };
+        if (sub == 0) {
 #pragma unroll
-        for (int g = 0; g < kFoldInRegs; ++g)
-            if (g < NG) fold(fw[g]);
-        for (int g = kFoldInRegs; g < NG; ++g) fold(tabi[tl.fold + g * P::G + lg]);
+            for (int g = 0; g < kFoldInRegs; ++g)
+                if (g < NG) fold(fw[g]);
+            for (int g = kFoldInRegs; g < NG; ++g) fold(tabi[tl.fold + g * P::GF + (lg % P::GF)]);
+        }
+        if constexpr (P::WPL > 1) __syncthreads();
         // 1c. gather: first and second coordinate of each of this lane's buckets
         float2 v[P::R];
 #pragma unroll
@@ -496,14 +519,14 @@ __global__ __launch_bounds__(64 * M) __attribute__((amdgpu_waves_per_eu(Plan<LOG
     }
     __syncthreads();
     fft.run(my_slot);
-    wave_lds_fence();
+    transform_fence<P>();
     float *row = out + n * ld_out;
     if (tid == 0) row[0] = 1.0f;
     const float invD = 1.0f / (float)D;
     // Dout buckets per level. Dout == D: the transform was circular in D already. Dout < D (a bucket
     // count that is no power of two): D was chosen so large that the M-fold convolution never wrapped,
     // and the linear result is folded modulo Dout here.
-    for (int j = lane; j < Dout; j += 64) {
+    for (int j = sub * 64 + lane; j < Dout; j += 64 * P::WPL) {
         float acc = 0.f;
         for (int e = j; e < D; e += Dout) acc += wave_lds[pad(e)].x;
         row[1 + (int64_t)m * Dout + j] = acc * invD;
