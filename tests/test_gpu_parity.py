@@ -70,7 +70,9 @@ def test_small_64_rows(oracle):
     (3, 300, 33, 3, 130, 512),  # d above one MFMA K-slab, F with a ragged column tile
     (1, 1000, 2, 5, 16, 8),     # long and narrow
     (3, 24, 6, 5, 100, 1024),   # D = 1024, three-pass transform
-    (2, 11, 4, 2, 300, 2048),   # D = 2048, 32 points per lane
+    (2, 11, 4, 2, 300, 2048),   # D = 2048: one transform per pair of wavefronts
+    (1, 6, 2, 8, 16, 2048),     # D = 2048 with eight levels: 1024 threads, 155 KB of LDS
+    (2, 5, 3, 5, 1100, 2048),   # D = 2048 with more coordinates than buckets: several staging batches per wavefront
     (2, 40, 3, 8, 20, 256),     # eight levels
     (2, 30, 3, 9, 12, 64),      # nine levels: generic kernel
     (3, 50, 5, 7, 33, 128),     # seven levels, D = 128
@@ -235,6 +237,7 @@ def test_symmetric_gram_path(oracle, N, C):
     (3, 12, 2, 2, 8, 6),        # tiny: generic kernel, transform length 16
     (2, 9, 3, 4, 16, 3),        # D = 3
     (2, 30, 3, 2, 50, 1000),    # 2048
+    (2, 9, 3, 5, 40, 300),      # 2048 through five levels
     (2, 7, 2, 3, 5, 1),         # a single bucket
 ])
 def test_bucket_counts_that_are_no_power_of_two(oracle, N, L, d, M, F, D):
