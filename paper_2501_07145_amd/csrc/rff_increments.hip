@@ -47,10 +47,13 @@ __device__ __forceinline__ void sincos_difference_store(
     AngleOf angle, const ScaledCoeffs &coeffs, float &carry_c, float &carry_s, int half, bool f_ok, int nrow,
     int64_t gt, int64_t g0, int64_t rf, int F, float *__restrict__ level_base, int f)
 {
-    const bool interior = nrow == kRowsPerTile && gt > g0;      // wavefront-uniform
-    float *cos_base = level_base + (gt - 1) * rf;               // uniform
+    // One store path for every tile: scalar base + 32-bit lane offset. The first row of a range has no
+    // increment to store (it belongs to the previous range) and rows past the end of the range do not
+    // exist; both cases are lane-uniform per row and folded into one predicate per store.
+    float *cos_base = level_base + (gt - 1) * rf;               // uniform (gt = g0: row -1 is never stored)
     float *sin_base = cos_base + F;
     const uint32_t lane_off = (uint32_t)f + (uint32_t)(4 * half) * (uint32_t)rf;
+    const int first = gt > g0 ? 0 : 1;                          // first tile row whose increment is ours
     float below_c = carry_c, below_s = carry_s;                 // lower half: partner's previous block
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -65,20 +68,11 @@ __device__ __forceinline__ void sincos_difference_store(
         for (int i = 0; i < 4; ++i) {
             const float dc = cs[i] - (i ? cs[i - 1] : up_c);
             const float ds = sn[i] - (i ? sn[i - 1] : up_s);
-            if (interior) {
-                if (f_ok) {
-                    const uint32_t off = lane_off + (uint32_t)(8 * q + i) * (uint32_t)rf;
-                    cos_base[off] = dc;
-                    sin_base[off] = ds;
-                }
-            } else {
-                const int r = 8 * q + 4 * half + i;
-                const int64_t g = gt + r;
-                if (f_ok && r < nrow && g > g0) {
-                    float *dst = level_base + f + (g - 1) * rf;
-                    dst[0] = dc;
-                    dst[F] = ds;
-                }
+            const int r = 8 * q + 4 * half + i;
+            if (f_ok && r >= first && r < nrow) {
+                const uint32_t off = lane_off + (uint32_t)(8 * q + i) * (uint32_t)rf;
+                cos_base[off] = dc;
+                sin_base[off] = ds;
             }
         }
     }
