@@ -145,7 +145,9 @@ __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
 // level. rank(a) = number of earlier coordinates of the level in the same bucket; ranks 0 and 1
 // go to the gather words, ranks >= 2 become fold entries, ordered by rank and padded so that a
 // round of G entries never mixes two ranks (hence never repeats a bucket).
-__global__ __launch_bounds__(256) void build_tables_kernel(
+constexpr int kTableThreads = 1024;
+
+__global__ __launch_bounds__(1024) void build_tables_kernel(
     const int32_t *__restrict__ hash, const float *__restrict__ sign, int twoF, int D, int Dout, int G, int LOADB,
     int PD, uint32_t *__restrict__ table)
 {
@@ -158,12 +160,12 @@ __global__ __launch_bounds__(256) void build_tables_kernel(
     uint32_t *tab = table + (int64_t)m * tl.words;
     const uint32_t zero_off = (uint32_t)tuned::zero_slot(PD, twoF) * 8u;
 
-    for (int a = tid; a < twoF; a += 256) h[a] = ((hash[(int64_t)m * twoF + a] % Dout) + Dout) % Dout;
-    for (int e = tid; e < D; e += 256) { src0[e] = -1; src1[e] = -1; }
-    for (int r = tid; r <= twoF; r += 256) cls[r] = 0;
+    for (int a = tid; a < twoF; a += kTableThreads) h[a] = ((hash[(int64_t)m * twoF + a] % Dout) + Dout) % Dout;
+    for (int e = tid; e < D; e += kTableThreads) { src0[e] = -1; src1[e] = -1; }
+    for (int r = tid; r <= twoF; r += kTableThreads) cls[r] = 0;
     if (tid == 0) max_rank = 0;
     __syncthreads();
-    for (int a = tid; a < twoF; a += 256) {
+    for (int a = tid; a < twoF; a += kTableThreads) {
         const int ha = h[a];
         int r = 0, a2 = 0;
         for (; a2 + 8 <= a; a2 += 8) {              // wide LDS reads keep the loop off the LDS latency
@@ -188,13 +190,13 @@ __global__ __launch_bounds__(256) void build_tables_kernel(
         tab[0] = (uint32_t)n_rounds;
     }
     __syncthreads();
-    for (int i = tid; i < n_rounds * G; i += 256) tab[tl.fold + i] = zero_off | (tuned::kFoldPad << 16);
-    for (int e = tid; e < D; e += 256) {
+    for (int i = tid; i < n_rounds * G; i += kTableThreads) tab[tl.fold + i] = zero_off | (tuned::kFoldPad << 16);
+    for (int e = tid; e < D; e += kTableThreads) {
         const uint32_t s0 = src0[e] >= 0 ? (uint32_t)src0[e] * 8u : zero_off;
         const uint32_t s1 = src1[e] >= 0 ? (uint32_t)src1[e] * 8u : zero_off;
         tab[tl.gather + e] = s0 | (s1 << 16);
     }
-    for (int i = tid; i < tl.nbatch * 64; i += 256) {
+    for (int i = tid; i < tl.nbatch * 64; i += kTableThreads) {
         const int bi = i >> 6, lane = i & 63;
         uint32_t w = 0;
         for (int b = 0; b < LOADB; ++b) {
@@ -204,7 +206,7 @@ __global__ __launch_bounds__(256) void build_tables_kernel(
         tab[tl.signs + i] = w;
     }
     __syncthreads();                      // padding entries are in place before the real ones land
-    for (int a = tid; a < twoF; a += 256) {
+    for (int a = tid; a < twoF; a += kTableThreads) {
         const int r = rk[a];
         if (r < 2) continue;
         int idx = 0, a2 = 0;
@@ -291,7 +293,7 @@ hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int
             granted = lds;
         }
     }
-    hipLaunchKernelGGL(build_tables_kernel, dim3((unsigned)M), dim3(256), lds, stream, hash, sign, twoF, D, Dout,
+    hipLaunchKernelGGL(build_tables_kernel, dim3((unsigned)M), dim3(kTableThreads), lds, stream, hash, sign, twoF, D, Dout,
                        g.G, g.LOADB, g.PD, table);
     return hipGetLastError();
 }
