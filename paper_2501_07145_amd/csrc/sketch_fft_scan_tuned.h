@@ -15,16 +15,17 @@
 //        ds_add_f32 costs ~190 cycles on this chip), no clearing, and the summation order is
 //        fixed, so results are bit-reproducible.
 //     2. FPW complex FFTs of length D held in the wavefront's LDS slots, G = D/R lanes per
-//        transform with R points per lane in registers (Stockham passes, radix up to 32 in
-//        registers, one LDS exchange per pass, no workgroup barrier inside the transform),
+//        transform with R = 16 points per lane in registers (Stockham passes, radix up to 16 in
+//        registers, one LDS exchange per pass; no workgroup barrier inside the transform unless it
+//        spans two wavefronts),
 //   then, after one barrier, every thread owns a few frequency bins, separates the two real
 //   transforms of each slot, and advances the accumulators A_1..A_M of its bins by the two
 //   time steps (A_m += A_{m-1}(before the step) * C_m, A_0 = 1; with signature order 2 also
 //   + 1/2 A_{m-2}(before the step) * C_{m-1} * C_m, Sec. 3.5 eq. (ts_rec) with q = 2).
 //   After the last time step, wavefront m transforms A_m back and writes block m of the row.
-//   (Fetching the next iteration's rows early was tried: the 32 extra live registers cost more
-//   in occupancy or spills than the hidden latency gains; workgroups of other sequences on the
-//   same CU hide it instead.)
+//   (Fetching the next iteration's rows ahead of time was tried in several placements and was never
+//   faster: the pace is set by the instruction streams of the resident workgroups, not by the load
+//   latency of one of them. What did pay off every time was more resident wavefronts.)
 //
 // The increments arrive pre-multiplied by 1/2 (done by the producing kernel), which is the
 // factor of the two-for-one separation  C0 = (Z[f] + conj Z[D-f]) / 2,  C1 = (Z[f] - conj Z[D-f]) / 2i.
