@@ -100,3 +100,22 @@ def test_full_size(oracle, name, n_oracle, n_identity):
     if not w.N2:
         Ksub = K[torch.from_numpy(sel).cuda()][:, torch.from_numpy(sel).cuda()].cpu().numpy()
         assert gram_error(Ksub, oracle.gram(want)) <= (5 * GRAM_TOL if w.rff_bf16 else GRAM_TOL)
+
+
+def test_hundred_thousand_time_points(oracle):
+    """The paper's scalability claim for the primal methods is sequence length 1e5 and beyond (Sec. 4).
+    Two sequences of 100001 points in the paper's own shape (d = 5, M = 5, feature and projection size
+    100); the accumulators run through 1e5 steps in fp32 and must stay within the tolerance."""
+    N, L, d, M, F, D = 2, 100001, 5, 5, 50, 100
+    rng = np.random.default_rng(0)
+    X = np.cumsum(rng.standard_normal((N, L, d)) / math.sqrt(L), axis=1).astype(np.float32)
+    W = rng.standard_normal((M, d, F)).astype(np.float32)
+    hash_ = rng.integers(0, D, size=(M, 2 * F)).astype(np.int32)
+    sign = (2.0 * rng.integers(0, 2, size=(M, 2 * F)) - 1.0).astype(np.float32)
+    ls = float(np.float32(math.sqrt(d)))
+    got = rfsf.rfsf_ts_features(torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(),
+                                torch.from_numpy(hash_).cuda(), torch.from_numpy(sign).cuda(), ls, D)
+    torch.cuda.synchronize()
+    err = block_errors(got.cpu().numpy(), oracle.features(X, W, hash_, sign, ls, D), M, D)
+    print("L = 100001: block errors", err)
+    assert np.all(err <= FP32_BLOCK_TOL)
