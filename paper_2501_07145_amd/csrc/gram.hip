@@ -61,16 +61,22 @@ constexpr int kLdsStride = kKT + 4; // floats per LDS row: 16 consecutive rows s
 // Needs 16-byte aligned bases and leading dimensions that are multiples of 4.
 // SYM: PhiY is PhiX. Only the tiles on or above the diagonal are computed (blockIdx.x enumerates
 // them row by row); mirror_lower_kernel fills in the rest afterwards.
-template <int WT, bool SYM>
-__global__ __launch_bounds__(256) void gram_mfma(
+// KS = 2 (small problems only, WT = 1): a second group of four wavefronts takes every other K slab with
+// its own LDS staging, so that a CU that gets a single tile still has two wavefronts per SIMD; the two
+// partial tiles are added through LDS at the end, in a fixed order.
+template <int WT, bool SYM, int KS = 1>
+__global__ __launch_bounds__(256 * KS) void gram_mfma(
     const float *__restrict__ A, int64_t Nx, int64_t lda, const float *__restrict__ B, int64_t Ny,
     int64_t ldb, int64_t K, float *__restrict__ C, int64_t ldc)
 {
     constexpr int TILE = 64 * WT;               // rows of A (and of B) per workgroup
     constexpr int NLD = TILE * (kKT / 4) / 256; // float4 loads per thread per operand per slab
-    __shared__ float As[TILE * kLdsStride];
-    __shared__ float Bs[TILE * kLdsStride];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ __attribute__((aligned(16))) float As_all[KS * TILE * kLdsStride];
+    __shared__ __attribute__((aligned(16))) float Bs_all[KS * TILE * kLdsStride];
+    __shared__ float red[KS == 2 ? 16 * 256 : 1];       // partial tile of the second K-split group
+    const int group = threadIdx.x / 256;                 // K-split group (0 when KS = 1)
+    float *As = As_all + group * TILE * kLdsStride, *Bs = Bs_all + group * TILE * kLdsStride;
+    const int tid = threadIdx.x % 256, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
     const int wi = wave >> 1, wj = wave & 1;
     int64_t bi = blockIdx.y, bj = blockIdx.x;
@@ -122,12 +128,15 @@ __global__ __launch_bounds__(256) void gram_mfma(
         }
     };
 
-    fetch(0);
-    for (int64_t k0 = 0; k0 < K; k0 += kKT) {
+    // group g takes slabs g, g + KS, ...; a slab past the end is fetched as zeros, so that every group
+    // runs the same number of iterations (the barriers are workgroup-wide)
+    fetch((int64_t)group * kKT);
+    for (int64_t kb = 0; kb < K; kb += (int64_t)KS * kKT) {
+        const int64_t k0 = kb + (int64_t)group * kKT;
         __syncthreads();                                 // previous slab fully consumed
         stage();
         __syncthreads();
-        if (k0 + kKT < K) fetch(k0 + kKT);
+        if (kb + (int64_t)KS * kKT < K) fetch(k0 + (int64_t)KS * kKT);
         // this lane's 16 columns of each of its rows: physical columns 16*half .. 16*half+15
         float4 fa[WT][4], fb[WT][4];
 #pragma unroll
@@ -149,6 +158,18 @@ __global__ __launch_bounds__(256) void gram_mfma(
                         const float bv = e == 0 ? fb[b][c].x : e == 1 ? fb[b][c].y : e == 2 ? fb[b][c].z : fb[b][c].w;
                         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[a][b], 0, 0, 0);
                     }
+    }
+    if constexpr (KS == 2) {                            // group 1 hands its partial tile to group 0
+        static_assert(WT == 1 || KS == 1, "the K split is for the single-block tile only");
+        __syncthreads();
+        if (group == 1) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[v * 256 + tid] = acc[0][0][v];
+        }
+        __syncthreads();
+        if (group == 1) return;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[0][0][v] += red[v * 256 + tid];
     }
     // result layout of a 32x32 block: lane holds column lane%32 and rows 8q + 4*(lane/32) + i
 #pragma unroll
@@ -214,7 +235,13 @@ hipError_t launch_gram(const float *PhiX, int64_t Nx, int64_t ldx, const float *
             hipLaunchKernelGGL((gram_mfma<2, false>), g, dim3(256), 0, stream, PhiX, Nx, ldx, PhiY, Ny, ldy, ncols, K, ldk);
         } else {
             dim3 g((unsigned)((Ny + 63) / 64), (unsigned)((Nx + 63) / 64));
-            hipLaunchKernelGGL((gram_mfma<1, false>), g, dim3(256), 0, stream, PhiX, Nx, ldx, PhiY, Ny, ldy, ncols, K, ldk);
+            const int64_t small_tiles = (int64_t)g.x * g.y;
+            if (small_tiles <= 512 && ncols >= 256)     // at most two tiles per CU: split K inside the workgroup
+                hipLaunchKernelGGL((gram_mfma<1, false, 2>), g, dim3(512), 0, stream, PhiX, Nx, ldx, PhiY, Ny, ldy,
+                                   ncols, K, ldk);
+            else
+                hipLaunchKernelGGL((gram_mfma<1, false>), g, dim3(256), 0, stream, PhiX, Nx, ldx, PhiY, Ny, ldy,
+                                   ncols, K, ldk);
         }
         return hipGetLastError();
     }

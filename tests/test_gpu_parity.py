@@ -228,7 +228,7 @@ def test_symmetric_gram_path(oracle, N, C):
     assert torch.equal(K, K.T.contiguous())
     K2 = rfsf.rfsf_ts_gram(Ad, Ad.clone())                 # two operands: the general path
     torch.cuda.synchronize()
-    assert gram_error(K2.cpu().numpy(), K.cpu().numpy()) <= 1e-6
+    assert gram_error(K2.cpu().numpy(), K.cpu().numpy()) <= 1e-5       # different kernels, different summation order
 
 
 @pytest.mark.parametrize("N,L,d,M,F,D", [
