@@ -14,7 +14,6 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kRows = 32;          // time points per tile
-constexpr int kMaxLevels = 16;     // accumulators per thread kept in LDS
 
 // Workgroup = (sequence, slab of 256 components), four wavefronts of 64 components each. Per tile of
 // 32 time points and per level: theta = X_tile * W_m on the matrix cores (two 32x32 blocks per
@@ -29,7 +28,9 @@ __global__ __launch_bounds__(256) void dp1d_features_kernel(
     constexpr int KP = 2 * KSTEPS, XS = KP | 1;
     __shared__ float xs[2 * kRows * XS];
     __shared__ float tile[4][kRows][65];
-    __shared__ float acc_state[kMaxLevels][256], cos_state[kMaxLevels][256];
+    extern __shared__ float level_state[];             // [2][M][256]: accumulators, then last cosines
+    float (*acc_state)[256] = reinterpret_cast<float (*)[256]>(level_state);
+    float (*cos_state)[256] = reinterpret_cast<float (*)[256]>(level_state + (size_t)M * 256);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
     const int64_t n = blockIdx.x;
@@ -127,7 +128,7 @@ hipError_t launch_dp1d(const float *X, const float *W, const float *bias, float 
     if (N == 0) return hipSuccess;
     dim3 grid((unsigned)N, (unsigned)((F + 255) / 256));
 #define RFSF_LAUNCH_DP1D(KS)                                                                                  \
-    hipLaunchKernelGGL(dp1d_features_kernel<KS>, grid, dim3(256), 0, stream, X, W, bias, inv_lengthscale, L, \
+    hipLaunchKernelGGL(dp1d_features_kernel<KS>, grid, dim3(256), sizeof(float) * 2 * M * 256, stream, X, W, bias, inv_lengthscale, L, \
                        d, M, F, out, ld_out)
     if (d <= 4) RFSF_LAUNCH_DP1D(2);
     else if (d <= 8) RFSF_LAUNCH_DP1D(4);
