@@ -6,6 +6,8 @@
 namespace rfsf {
 namespace {
 
+constexpr int kCached = 32;        // values per lane held in registers (blocks up to 2048 numbers)
+
 // One workgroup per row, one wavefront per level at a time (levels strided over the 4 wavefronts).
 __global__ __launch_bounds__(256) void normalize_rows_kernel(float *__restrict__ Phi, int64_t ld, int M, int D)
 {
@@ -15,13 +17,34 @@ __global__ __launch_bounds__(256) void normalize_rows_kernel(float *__restrict__
     if (threadIdx.x == 0) row[0] *= w;
     for (int m = wave; m < M; m += 4) {
         float *blk = row + 1 + (int64_t)m * D;
-        float ss = 0.f;
-        for (int j = lane; j < D; j += 64) ss = fmaf(blk[j], blk[j], ss);
+        if (D <= 64 * kCached) {                   // the block fits in registers: read once, write once
+            float buf[kCached];
+            float ss = 0.f;
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
-        if (ss > 0.f) {
-            const float f = w / sqrtf(ss);
-            for (int j = lane; j < D; j += 64) blk[j] *= f;
+            for (int i = 0; i < kCached; ++i) {
+                const int j = lane + 64 * i;
+                buf[i] = j < D ? blk[j] : 0.f;
+                ss = fmaf(buf[i], buf[i], ss);
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+            if (ss > 0.f) {
+                const float f = w / sqrtf(ss);
+#pragma unroll
+                for (int i = 0; i < kCached; ++i) {
+                    const int j = lane + 64 * i;
+                    if (j < D) blk[j] = buf[i] * f;
+                }
+            }
+        } else {
+            float ss = 0.f;
+            for (int j = lane; j < D; j += 64) ss = fmaf(blk[j], blk[j], ss);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+            if (ss > 0.f) {
+                const float f = w / sqrtf(ss);
+                for (int j = lane; j < D; j += 64) blk[j] *= f;
+            }
         }
     }
 }
