@@ -96,6 +96,7 @@ int64_t chunk_for(const rfsf_ts_shape *s, size_t bytes)
 struct SideStream {
     hipStream_t stream = nullptr;
     hipEvent_t begin = nullptr, done = nullptr;
+    int device = -1;            // the device the stream and events belong to
     bool usable = false;
 };
 SideStream &side_stream()
@@ -104,11 +105,17 @@ SideStream &side_stream()
     static bool tried = false;
     if (!tried) {
         tried = true;
-        s.usable = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
+        s.usable = hipGetDevice(&s.device) == hipSuccess &&
+                   hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
                    hipEventCreateWithFlags(&s.begin, hipEventDisableTiming) == hipSuccess &&
                    hipEventCreateWithFlags(&s.done, hipEventDisableTiming) == hipSuccess;
     }
     return s;
+}
+bool side_stream_matches_current_device(const SideStream &s)
+{
+    int dev = -1;
+    return s.usable && hipGetDevice(&dev) == hipSuccess && dev == s.device;
 }
 
 }  // namespace
@@ -189,7 +196,7 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
     uint32_t *table = reinterpret_cast<uint32_t *>(p_table);
     SideStream &side = side_stream();
     bool tables_on_side = false;
-    if (side.usable && hipEventRecord(side.begin, stream) == hipSuccess &&
+    if (side_stream_matches_current_device(side) && hipEventRecord(side.begin, stream) == hipSuccess &&
         hipStreamWaitEvent(side.stream, side.begin, 0) == hipSuccess) {
         if (rfsf::launch_pack_tables(hash, sign, shape->M, shape->F, P, shape->D, table, side.stream) != hipSuccess)
             return RFSF_E_HIP;
