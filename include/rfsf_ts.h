@@ -17,7 +17,9 @@
  *     nothing that the caller sees.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is the
  *     default stream). The calls do not synchronise the device; results are
- *     ready when the stream has drained.
+ *     ready when the stream has drained. (rfsf_ts_features builds its sketch tables
+ *     on a stream the library owns, forked from and joined back into `hip_stream`
+ *     with events, so the ordering seen by the caller is that of `hip_stream`.)
  *   - Return value: RFSF_OK (0) or a negative RFSF_E_* code. After an argument
  *     error nothing has been enqueued and no output byte has been written.
  */
@@ -64,15 +66,16 @@ const char *rfsf_ts_strerror(int code);
  *   *recommended_bytes : size at which the whole batch (or a large chunk of it) is
  *                        processed per kernel launch;
  *   *minimum_bytes     : smallest size accepted (one chunk of sequences).
- * Either output pointer may be NULL. The workspace holds the time increments of
- * the random Fourier features of one chunk of sequences (Sec. 3.2, eq. (rfsf),
- * the factors nabla phi_m) between the two kernels; its layout is private.
+ * Either output pointer may be NULL. The workspace holds the per-call sketch tables and
+ * the time increments of the random Fourier features of one chunk of sequences
+ * (Sec. 3.2, eq. (rfsf), the factors nabla phi_m) between the two kernels; its layout is
+ * private.
  */
 int rfsf_ts_workspace_bytes(const rfsf_ts_shape *shape,
                             size_t *recommended_bytes, size_t *minimum_bytes);
 
 /*
- * RFSF-TS feature map (Sec. 3.5, eqs. (cs), (ts_def), (ts), (ts_rec) with p = 1, on
+ * RFSF-TS feature map (Sec. 3.5, eqs. (cs), (ts_def), (ts), (ts_rec), order p = shape->order, on
  * top of the random Fourier features of Sec. 3.1, eq. (rff), one independent map
  * per level as in Sec. 3.2).
  *
