@@ -118,7 +118,8 @@ __host__ __device__ inline TableLayout table_layout(int D, int G, int LOADB, int
     return t;
 }
 constexpr uint32_t kFoldPad = 0xffffu;
-constexpr int kFoldInRegs = 2;
+constexpr int kFoldInRegs = 4;      // fold rounds whose entries are fetched with the other tables; later rounds load
+                                    // theirs on the spot (4 measured best of 2, 4, 6, 8)
       // fold rounds whose entries are fetched with the other tables
 
 // cos(k pi / 16), k = 0..8
