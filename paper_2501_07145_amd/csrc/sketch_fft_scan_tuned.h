@@ -120,7 +120,6 @@ __host__ __device__ inline TableLayout table_layout(int D, int G, int LOADB, int
 constexpr uint32_t kFoldPad = 0xffffu;
 constexpr int kFoldInRegs = 4;      // fold rounds whose entries are fetched with the other tables; later rounds load
                                     // theirs on the spot (4 measured best of 2, 4, 6, 8)
-      // fold rounds whose entries are fetched with the other tables
 
 // cos(k pi / 16), k = 0..8
 __device__ constexpr float kCos16[9] = {1.0f, 0.98078528040323043f, 0.92387953251128674f, 0.83146961230254524f,
