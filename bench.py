@@ -29,18 +29,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 MFMA_FP32_PEAK_TFLOPS = 157.3    # MI355X dense fp32 matrix, published
 
-# HBM bytes per kernel launch measured with rocprofv3 (FETCH_SIZE * 2.000 + WRITE_SIZE * 1.000 KiB, the
-# factors calibrated on a plain 1 GiB device copy in the same run; summaries: profiles/hbm_traffic_*.txt).
-# These are measurements of the kernels as committed with those summaries, not computed here; a workload
-# without an entry reports null.
-MEASURED_TRAFFIC_KIB = {
-    ("small", "rff_increments"): 6553.1 * 2 + 399996.0,
-    ("small", "sketch_fft_scan"): 198150.3 * 2 + 4031.2,
-    ("small", "gram"): 16097.7 * 2 + 3906.2,
-    ("medium", "rff_increments"): 295188.8 * 2 + 19999980.0,
-    ("medium", "sketch_fft_scan"): 9950257.0 * 2 + 112659.7,
-    ("medium", "gram"): 6840837.4 * 2 + 210923.2,     # the matrix-core kernel; the mirror pass adds ~0.4 GB
-}
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix, published
 
 
 VALU_FP32_PEAK_TFLOPS = 157.3    # MI355X fp32 vector, published (needs packed fp32; 78.6 without)
@@ -211,52 +200,55 @@ def bench_trp(args, w, inp, dev, ls) -> int:
     return 0
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 300 for tiny/small, 20 for medium/long, 5 for large)")
-    ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default: 50 / 3 / 1)")
-    ap.add_argument("--workload", default="small", choices=["tiny", "small", "medium", "long", "large", "paper"])
-    ap.add_argument("--cpu-rows", type=int, default=-1, help="oracle sample size (-1: per-workload default)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--variant", default="ts", choices=["ts", "dp1d", "trp"],
-                    help="ts: the tensor-sketch path (default, the headline metric); dp1d: the sibling RFSF-DP-1D "
-                         "variant (one fused kernel, features [N, 1+M*F]) plus its Gram; trp: the sibling RFSF-TRP variant "
-                         "(Q = D Gaussian projections per level) plus its Gram")
-    ap.add_argument("--normalize", action="store_true",
-                    help="add the level-wise normalisation of the features to the step (not part of the default path)")
-    ap.add_argument("--copy-probe-mib", type=int, default=0,
-                    help="after the timed steps run one plain device copy of this many MiB (calibrates the "
-                         "FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
-    args = ap.parse_args()
-    if args.steps is None:
-        args.steps = {"tiny": 300, "small": 300, "large": 5}.get(args.workload, 20)
-    if args.warmup is None:
-        args.warmup = {"tiny": 50, "small": 50, "large": 1}.get(args.workload, 3)
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (sequences are independent; sharding N over "
-              "GPUs is design-only). Run with --gpus 1.", file=sys.stderr)
-        return 2
+def _kernel_source_digest() -> str:
+    """Digest of the kernel sources the loaded library was built from; ties a stored rocprofv3 traffic figure to
+    the code it was measured on."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_2501_07145_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h", ".inc")):
+            h.update(name.encode())
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()[:16]
 
+
+def _measured_traffic(workload: str) -> dict:
+    """HBM bytes per kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this workload
+    (profiles/hbm_traffic_<workload>.txt, lines `traffic_bytes_per_launch <kernel> <bytes>`), or {} when there
+    is none or when it was measured on other kernel sources than the ones in this tree."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return {}
+    digest, out = None, {}
+    with open(path) as f:
+        for line in f:
+            t = line.split()
+            if len(t) == 2 and t[0] == "kernel_sources_sha256":
+                digest = t[1]
+            elif len(t) == 3 and t[0] == "traffic_bytes_per_launch":
+                out[t[1]] = float(t[2])
+    return out if digest == _kernel_source_digest() else {}
+
+
+def bench_ts(args, name: str, steps: int, warmup: int, cpu_baseline: bool) -> dict:
+    """One workload through the tensor-sketch path: features (+ second batch) + Gram; returns the result dict."""
     import numpy as np
     import torch
 
     import paper_2501_07145_amd as rfsf
     from paper_2501_07145_amd import workloads as wl
 
-    torch.cuda.set_device(0)
-    w = wl.WORKLOADS[args.workload]
+    w = wl.WORKLOADS[name]
     inp = wl.make_inputs(w, 0)
     dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items() if isinstance(v, np.ndarray)}
     ls = inp["lengthscale"]
     X2 = torch.from_numpy(wl.make_paths(w.scaled(N=w.N2), 1)).cuda() if w.N2 else None
 
-    if args.variant == "dp1d":
-        return bench_dp1d(args, w, inp, dev, ls)
-    if args.variant == "trp":
-        return bench_trp(args, w, inp, dev, ls)
-
     rec_bytes, _ = rfsf.rfsf_ts_workspace_bytes(w.N, w.L, w.d, w.M, w.F, w.D, w.rff_bf16)
+    if args.workspace_mib > 0:
+        rec_bytes = args.workspace_mib << 20
     workspace = torch.empty(rec_bytes, dtype=torch.uint8, device="cuda")
     ld = rfsf.feature_row_stride(w.M, w.D)
     out = torch.empty((w.N, ld), dtype=torch.float32, device="cuda")[:, :w.ncols]
@@ -277,18 +269,18 @@ def main() -> int:
         else:
             rfsf.rfsf_ts_gram(out, K=K)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
-    t_step = (time.perf_counter() - t0) / args.steps
+    t_step = (time.perf_counter() - t0) / steps
 
     # same K steps again with per-kernel HIP events on the launch stream
     rfsf.rfsf_ts_profile_enable(True)
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     prof = rfsf.rfsf_ts_profile_read(reset=True)
@@ -301,26 +293,40 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    units = (w.N + w.N2) * w.L                       # sequence-steps per step
-    incr_bytes_per_unit = 4.0 * w.M * 2 * w.F          # fp32 increments written by one kernel, read by the next
     n_seq = w.N + w.N2
+    units = n_seq * w.L                              # the metric's unit: sequences x time points
+    incr_units = n_seq * (w.L - 1)                   # increments: what the kernels between X and out move
+    incr_bytes = 4.0 * w.M * 2 * w.F                 # fp32 increments of one time step, all levels
+    traffic = _measured_traffic(w.name)
     kernels = {}
 
-    def entry(name, bound, work_per_step, unit, peak):
-        n = prof[f"launches_{name}"]
+    def entry(kname, bound, work_per_step, unit, peak, **extra):
+        n = prof[f"launches_{kname}"]
         if n == 0:
             return
-        avg_ms = prof[f"ms_{name}"] / n
-        per_launch = work_per_step * args.steps / n
+        avg_ms = prof[f"ms_{kname}"] / n
+        per_launch = work_per_step * steps / n
         achieved = per_launch / (avg_ms * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
-        kib = MEASURED_TRAFFIC_KIB.get((w.name, name))
-        kernels[name] = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                         "frac": achieved / peak, "traffic": None if kib is None else kib * 1024.0,
-                         "algorithmic_per_launch": per_launch, "avg_launch_ms": avg_ms,
-                         "launches_per_step": n / args.steps, "ms_per_step": prof[f"ms_{name}"] / args.steps}
+        kernels[kname] = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+                          "frac": achieved / peak, "traffic": traffic.get(kname),
+                          "algorithmic_per_launch": per_launch, "avg_launch_ms": avg_ms,
+                          "launches_per_step": n / steps, "ms_per_step": prof[f"ms_{kname}"] / steps}
+        t_s = prof[f"ms_{kname}"] / steps * 1e-3
+        for k, v in extra.items():
+            kernels[kname][k] = v / t_s
 
-    entry("rff_increments", "hbm", units * (4.0 * w.d + incr_bytes_per_unit), "GB/s", HBM_PEAK_GBS)
-    entry("sketch_fft_scan", "hbm", units * incr_bytes_per_unit + 4.0 * n_seq * w.M * w.D, "GB/s", HBM_PEAK_GBS)
+    # projection kernel: binding resources are the HBM write of the increments and the sin/cos arithmetic
+    # (K = d is tiny), so it is entered against the HBM roofline; the matrix-core share and the sin/cos rate
+    # are reported beside it
+    mfma_peak = MFMA_BF16_PEAK_TFLOPS if w.rff_bf16 else MFMA_FP32_PEAK_TFLOPS
+    proj_flops = (2.0 if w.rff_bf16 else 1.0) * 2.0 * w.d * w.M * w.F    # bf16: X enters as two bf16 terms
+    entry("rff_increments", "hbm", n_seq * 4.0 * w.L * w.d + incr_units * incr_bytes, "GB/s", HBM_PEAK_GBS,
+          mfma_tflops=units * proj_flops / 1e12, sincos_pairs_per_s=float(units * w.M * w.F),
+          write_gbs=incr_units * incr_bytes / 1e9)
+    if "rff_increments" in kernels:
+        kernels["rff_increments"]["mfma_peak"] = mfma_peak
+        kernels["rff_increments"]["mfma_frac"] = kernels["rff_increments"]["mfma_tflops"] / mfma_peak
+    entry("sketch_fft_scan", "hbm", incr_units * incr_bytes + 4.0 * n_seq * w.M * w.D, "GB/s", HBM_PEAK_GBS)
     Ny = w.N2 if w.N2 else w.N
     # flops the kernel performs: the whole matrix for a cross Gram; for K = Phi Phi^T of 2048+ rows
     # only the tiles on or above the diagonal (counted here as N(N+1)/2 inner products)
@@ -336,8 +342,8 @@ def main() -> int:
         "value": units / t_step,
         "unit": "sequences*steps/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": t_step * 1e3,
         "higher_is_better": True,
         "scaling": "weak",
@@ -352,7 +358,7 @@ def main() -> int:
         "kernels": kernels,
     }
 
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         import oracle
         from tests.parity import block_errors, gram_error
         default_rows = {"tiny": 16, "small": 1000, "medium": 32, "long": 16, "large": 32, "paper": 100}[w.name]
@@ -381,6 +387,84 @@ def main() -> int:
         }
         result["parity"] = {"rows": int(rows), "max_block_err_per_level": [float(e) for e in err],
                             "gram_err": gram_error(Ksel.cpu().numpy(), Kw)}
+    del workspace, out, out2, K, dev, X2
+    torch.cuda.empty_cache()
+    return result
+
+
+DEFAULT_STEPS = {"tiny": (300, 50), "small": (300, 50), "medium": (20, 3), "long": (20, 3), "large": (5, 1),
+                 "paper": (20, 3)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 300 for tiny/small, 20 for medium/long, 5 for large)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default: 50 / 3 / 1)")
+    ap.add_argument("--workload", default="medium", choices=["tiny", "small", "medium", "long", "large", "paper"],
+                    help="medium (default) is the largest configuration that runs in fp32 throughout")
+    ap.add_argument("--also", default=None,
+                    help="comma-separated further workloads measured after the headline one with their own default "
+                         "step counts and reported under 'other_workloads' (default: small,long,large when the "
+                         "headline is the default medium run, none otherwise; 'none' switches it off)")
+    ap.add_argument("--cpu-rows", type=int, default=-1, help="oracle sample size (-1: per-workload default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variant", default="ts", choices=["ts", "dp1d", "trp"],
+                    help="ts: the tensor-sketch path (default, the headline metric); dp1d: the sibling RFSF-DP-1D "
+                         "variant (one fused kernel, features [N, 1+M*F]) plus its Gram; trp: the sibling RFSF-TRP variant "
+                         "(Q = D Gaussian projections per level) plus its Gram")
+    ap.add_argument("--normalize", action="store_true",
+                    help="add the level-wise normalisation of the features to the step (not part of the default path)")
+    ap.add_argument("--workspace-mib", type=int, default=0,
+                    help="workspace size instead of the recommended one (sets the number of sequences per launch)")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="after the timed steps run one plain device copy of this many MiB (calibrates the "
+                         "FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
+    args = ap.parse_args()
+    default_run = args.workload == "medium" and args.variant == "ts" and not args.normalize and \
+        args.workspace_mib == 0 and args.copy_probe_mib == 0
+    if args.also is None:
+        args.also = "small,long,large" if default_run else "none"
+    if args.steps is None:
+        args.steps = DEFAULT_STEPS[args.workload][0]
+    if args.warmup is None:
+        args.warmup = DEFAULT_STEPS[args.workload][1]
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (sequences are independent; sharding N over "
+              "GPUs is design-only). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2501_07145_amd import workloads as wl
+
+    torch.cuda.set_device(0)
+    if args.variant != "ts":
+        w = wl.WORKLOADS[args.workload]
+        inp = wl.make_inputs(w, 0)
+        dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items() if isinstance(v, np.ndarray)}
+        if args.variant == "dp1d":
+            return bench_dp1d(args, w, inp, dev, inp["lengthscale"])
+        return bench_trp(args, w, inp, dev, inp["lengthscale"])
+
+    result = bench_ts(args, args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    others = [n for n in args.also.split(",") if n and n != "none" and n != args.workload]
+    if others:
+        # the other configurations, each at its own default step count, without the oracle leg: context for the
+        # headline line above, which stays the one the metric is quoted on
+        result["other_workloads"] = {}
+        for name in others:
+            if name not in wl.WORKLOADS:
+                print(f"bench.py: unknown workload {name!r} in --also", file=sys.stderr)
+                return 2
+            r = bench_ts(args, name, *DEFAULT_STEPS[name], False)
+            result["other_workloads"][name] = {
+                "value": r["value"], "ms_per_step": r["ms_per_step"], "steps": r["steps"], "dtype": r["dtype"],
+                "config": r["config"],
+                "kernels": {k: {f: v[f] for f in ("bound", "frac", "achieved", "unit", "avg_launch_ms",
+                                                   "launches_per_step") if f in v}
+                            for k, v in r["kernels"].items()}}
     print(json.dumps(result))
     return 0
 

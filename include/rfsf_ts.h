@@ -21,7 +21,13 @@
  *     on a stream the library owns, forked from and joined back into `hip_stream`
  *     with events, so the ordering seen by the caller is that of `hip_stream`.)
  *   - Return value: RFSF_OK (0) or a negative RFSF_E_* code. After an argument
- *     error nothing has been enqueued and no output byte has been written.
+ *     error (every code except RFSF_E_HIP) nothing has been enqueued and no output byte
+ *     has been written. After RFSF_E_HIP earlier kernels of the call may have been
+ *     enqueued; the outputs and the workspace are then unspecified, but nothing of the
+ *     library touches them any more once `hip_stream` has drained.
+ *   - Threads: the library keeps process-wide state (the side stream and its two events,
+ *     the optional profiling record) without locks. Calls from several host threads must
+ *     be serialised by the caller; calls from one thread on several streams are fine.
  */
 #ifndef RFSF_TS_H
 #define RFSF_TS_H
@@ -119,8 +125,8 @@ int rfsf_ts_validate_tables(const int32_t *hash, const float *sign,
                             int32_t M, int32_t F, int32_t D, void *hip_stream);
 
 /*
- * Linear Gram of primal features (Sec. 1, "K_XX = P_X P_X^T"; appendix, the feature
- * classes' call operator):
+ * Linear Gram of primal features (Sec. 1: the Gram matrix of a low-rank feature map is the
+ * product of the feature matrix with its transpose; appendix, the feature classes' call operator):
  *   K[i, j] = sum_{c < ncols} PhiX[i, c] * PhiY[j, c]          fp32 in, fp32 accumulate
  *
  *   PhiX [Nx, ldx], PhiY [Ny, ldy]  float32 row-major, ldx, ldy >= ncols (PhiY may equal PhiX)

@@ -90,6 +90,15 @@ def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
     return int(s.cuda_stream)
 
 
+def _empty_on(stream: Optional[torch.cuda.Stream], *args, **kwargs) -> torch.Tensor:
+    """torch.empty whose block belongs to `stream` for the caching allocator: memory the binding allocates is
+    used by kernels on that stream, possibly after this function has returned and dropped its reference."""
+    if stream is None:
+        return torch.empty(*args, **kwargs)
+    with torch.cuda.stream(stream):
+        return torch.empty(*args, **kwargs)
+
+
 def _dev(t: torch.Tensor, dtype: torch.dtype, name: str) -> torch.Tensor:
     if not t.is_cuda:
         raise ValueError(f"{name} must be a device tensor")
@@ -139,7 +148,7 @@ def rfsf_ts_features(X: torch.Tensor, W: torch.Tensor, hash: torch.Tensor, sign:
     ncols = 1 + M * int(D)
     if out is None:
         ld = feature_row_stride(M, int(D))
-        out = torch.empty((N, ld), dtype=torch.float32, device=X.device)[:, :ncols]
+        out = _empty_on(stream, (N, ld), dtype=torch.float32, device=X.device)[:, :ncols]
     if out.dim() != 2 or out.dtype != torch.float32 or not out.is_cuda or out.shape[0] != N or \
             out.shape[1] < ncols or (out.shape[1] > 0 and out.stride(1) != 1):
         raise ValueError("out must be float32 [N, >= 1+M*D] on the device with unit column stride")
@@ -147,7 +156,7 @@ def rfsf_ts_features(X: torch.Tensor, W: torch.Tensor, hash: torch.Tensor, sign:
     shp = _shape_of(X, W, hash, D, ld_out, rff_bf16, order)
     if workspace is None:
         rec, _ = rfsf_ts_workspace_bytes(shp.N, shp.L, shp.d, shp.M, shp.F, shp.D, rff_bf16)
-        workspace = torch.empty(rec, dtype=torch.uint8, device=X.device)
+        workspace = _empty_on(stream, rec, dtype=torch.uint8, device=X.device)
     workspace = _dev(workspace, torch.uint8, "workspace")
     _check(lib.rfsf_ts_features(ctypes.byref(shp), X.data_ptr(), W.data_ptr(), hash.data_ptr(),
                                 sign.data_ptr(), float(lengthscale), out.data_ptr(),
@@ -181,7 +190,7 @@ def rfsf_dp1d_features(X: torch.Tensor, W: torch.Tensor, bias: torch.Tensor, len
     M, _, F = W.shape
     ncols = 1 + M * F
     if out is None:
-        out = torch.empty((N, (ncols + 3) // 4 * 4), dtype=torch.float32, device=X.device)[:, :ncols]
+        out = _empty_on(stream, (N, (ncols + 3) // 4 * 4), dtype=torch.float32, device=X.device)[:, :ncols]
     if out.dim() != 2 or out.dtype != torch.float32 or not out.is_cuda or out.shape[0] != N or \
             out.shape[1] < ncols or (out.shape[1] > 0 and out.stride(1) != 1):
         raise ValueError("out must be float32 [N, >= 1+M*F] on the device with unit column stride")
@@ -214,7 +223,7 @@ def rfsf_trp_features(X: torch.Tensor, W: torch.Tensor, Z: torch.Tensor, lengths
     Q = Z.shape[1]
     ncols = 1 + M * Q
     if out is None:
-        out = torch.empty((N, (ncols + 3) // 4 * 4), dtype=torch.float32, device=X.device)[:, :ncols]
+        out = _empty_on(stream, (N, (ncols + 3) // 4 * 4), dtype=torch.float32, device=X.device)[:, :ncols]
     if out.dim() != 2 or out.dtype != torch.float32 or not out.is_cuda or out.shape[0] != N or \
             out.shape[1] < ncols or (out.shape[1] > 0 and out.stride(1) != 1):
         raise ValueError("out must be float32 [N, >= 1+M*Q] on the device with unit column stride")
@@ -222,7 +231,7 @@ def rfsf_trp_features(X: torch.Tensor, W: torch.Tensor, Z: torch.Tensor, lengths
     shp = _Shape(N, L, d, M, F, Q, ld_out, int(bool(rff_bf16)))
     if workspace is None:
         rec, _ = rfsf_trp_workspace_bytes(N, L, d, M, F, Q, rff_bf16)
-        workspace = torch.empty(rec, dtype=torch.uint8, device=X.device)
+        workspace = _empty_on(stream, rec, dtype=torch.uint8, device=X.device)
     workspace = _dev(workspace, torch.uint8, "workspace")
     _check(load_library().rfsf_trp_features(ctypes.byref(shp), X.data_ptr(), W.data_ptr(), Z.data_ptr(),
                                             float(lengthscale), out.data_ptr(), workspace.data_ptr(),
@@ -254,7 +263,7 @@ def rfsf_ts_gram(PhiX: torch.Tensor, PhiY: Optional[torch.Tensor] = None,
         raise ValueError("PhiX and PhiY need the same number of columns")
     Nx, Ny, ncols = PhiX.shape[0], PhiY.shape[0], PhiX.shape[1]
     if K is None:
-        K = torch.empty((Nx, Ny), dtype=torch.float32, device=PhiX.device)
+        K = _empty_on(stream, (Nx, Ny), dtype=torch.float32, device=PhiX.device)
     if K.dim() != 2 or K.dtype != torch.float32 or tuple(K.shape) != (Nx, Ny) or (Ny > 0 and K.stride(1) != 1):
         raise ValueError("K must be float32 [Nx, Ny] with unit column stride")
     ldx = PhiX.stride(0) if Nx > 1 else max(ncols, 1)

@@ -19,7 +19,7 @@ FLAGS = [
 ]
 
 
-EXTRA = os.environ.get("RFSF_EXTRA_HIPCC_FLAGS", "").split()   # for experiments, e.g. -DRFSF_PREFETCH=1
+EXTRA = os.environ.get("RFSF_EXTRA_HIPCC_FLAGS", "").split()   # extra compiler flags for experiments
 
 
 def _compile(src: str) -> str:

@@ -127,9 +127,22 @@ hipError_t launch_dp1d(const float *X, const float *W, const float *bias, float 
 {
     if (N == 0) return hipSuccess;
     dim3 grid((unsigned)N, (unsigned)((F + 255) / 256));
+    const size_t dyn = sizeof(float) * 2 * (size_t)M * 256;
+    // static LDS of the kernel (X double buffer + transposition tiles) plus the per-level state can pass
+    // 64 KB for many levels on a wide state; the limit on the dynamic part is then raised once per kernel
 #define RFSF_LAUNCH_DP1D(KS)                                                                                  \
-    hipLaunchKernelGGL(dp1d_features_kernel<KS>, grid, dim3(256), sizeof(float) * 2 * M * 256, stream, X, W, bias, inv_lengthscale, L, \
-                       d, M, F, out, ld_out)
+    do {                                                                                                      \
+        constexpr size_t kStatic = sizeof(float) * (2 * kRows * ((2 * KS) | 1) + 4 * kRows * 65);             \
+        static size_t raised = 0;                                                                             \
+        if (kStatic + dyn > 64 * 1024 && dyn > raised) {                                                      \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(dp1d_features_kernel<KS>),      \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);         \
+            if (e != hipSuccess) return e;                                                                    \
+            raised = dyn;                                                                                     \
+        }                                                                                                     \
+        hipLaunchKernelGGL(dp1d_features_kernel<KS>, grid, dim3(256), dyn, stream, X, W, bias,                \
+                           inv_lengthscale, L, d, M, F, out, ld_out);                                         \
+    } while (0)
     if (d <= 4) RFSF_LAUNCH_DP1D(2);
     else if (d <= 8) RFSF_LAUNCH_DP1D(4);
     else if (d <= 18) RFSF_LAUNCH_DP1D(9);

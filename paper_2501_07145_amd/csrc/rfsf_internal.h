@@ -7,14 +7,9 @@
 
 namespace rfsf {
 
-// Row g = n * L + t of the increment workspace holds, for every level m, the 2F numbers
+// Increment workspace: row g = n * L + t holds, for every level m, the 2F numbers
 // phi_m(x_{t+1}) - phi_m(x_t) of sequence n; rows with t = L-1 exist but are never read.
 // Element (g, m, a) sits at ((g * M + m) * 2F + a).
-struct IncrementLayout {
-    int64_t rows;      // N_chunk * L
-    int32_t M, F;
-    __host__ __device__ int64_t row_floats() const { return (int64_t)M * 2 * F; }
-};
 
 // Steps 1-2: random Fourier features of every time point and their time increments
 // for `n_seq` sequences starting at X (already offset to the chunk).
@@ -34,6 +29,7 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
 hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int F, int D, int Dout,
                               uint32_t *table, hipStream_t stream);
 bool sketch_fft_scan_is_tuned(int M, int F, int D);
+bool sketch_fft_scan_fits(int M, int F, int D, int order);  // false: neither kernel can run it (LDS need above a CU's)
 size_t sketch_fft_scan_table_bytes(int M, int F, int D);   // 0 when the generic kernel runs
 size_t sketch_fft_scan_lds_bytes(int M, int F, int D);
 size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D);

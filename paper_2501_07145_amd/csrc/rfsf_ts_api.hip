@@ -31,7 +31,11 @@ ProfileScope::~ProfileScope()
 namespace {
 
 constexpr size_t kAlign = 256;
-constexpr size_t kChunkBytesTarget = (size_t)32 << 30;   // increments held per launch, at most
+// Increments held per launch, at most. Measured on the N = 10000, L = 200, M = 5, F = 512 batch (41 GB of
+// increments): one launch 22.9 ms, two 23.5, four 24.6, sixteen 26.5, 64 launches of 0.64 GB 45 ms; a chunk
+// small enough for the last-level cache (64 sequences) cannot fill the chip, since the consumer runs one
+// workgroup per sequence. Hence: as few launches as a 48 GiB scratch allows.
+constexpr size_t kChunkBytesTarget = (size_t)48 << 30;
 constexpr size_t kIncrementTail = 4096;   // the sketch kernel may read up to 1023 floats past the last row
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -178,6 +182,8 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
     if (shape->rff_bf16 != 0 && shape->d > 128) return RFSF_E_UNSUPPORTED;
     if (shape->order > 2) return RFSF_E_UNSUPPORTED;
     if ((int64_t)shape->M * 2 * shape->F > ((int64_t)1 << 26)) return RFSF_E_UNSUPPORTED;   // 32-bit row offsets
+    if (!rfsf::sketch_fft_scan_fits(shape->M, shape->F, transform_length(shape->M, shape->D), shape->order == 2 ? 2 : 1))
+        return RFSF_E_UNSUPPORTED;        // the longest transform with order 2: more LDS than a CU has
     if (!workspace) return RFSF_E_NULLPTR;
     int64_t chunk = chunk_for(shape, workspace_bytes);
     if (chunk < 1) return RFSF_E_WORKSPACE_TOO_SMALL;
@@ -196,12 +202,23 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
     uint32_t *table = reinterpret_cast<uint32_t *>(p_table);
     SideStream &side = side_stream();
     bool tables_on_side = false;
+    // Error return after the fork: the caller's stream first waits for whatever the side stream still does
+    // (the table build writes the workspace), so that the workspace is quiet once `stream` has drained.
+    auto fail = [&]() {
+        if (tables_on_side) {
+            if (hipStreamWaitEvent(stream, side.done, 0) != hipSuccess) (void)hipStreamSynchronize(side.stream);
+        }
+        return RFSF_E_HIP;
+    };
     if (side_stream_matches_current_device(side) && hipEventRecord(side.begin, stream) == hipSuccess &&
         hipStreamWaitEvent(side.stream, side.begin, 0) == hipSuccess) {
-        if (rfsf::launch_pack_tables(hash, sign, shape->M, shape->F, P, shape->D, table, side.stream) != hipSuccess)
+        const hipError_t e = rfsf::launch_pack_tables(hash, sign, shape->M, shape->F, P, shape->D, table, side.stream);
+        if (hipEventRecord(side.done, side.stream) != hipSuccess) {
+            (void)hipStreamSynchronize(side.stream);
             return RFSF_E_HIP;
-        if (hipEventRecord(side.done, side.stream) != hipSuccess) return RFSF_E_HIP;
+        }
         tables_on_side = true;
+        if (e != hipSuccess) return fail();
     } else if (rfsf::launch_pack_tables(hash, sign, shape->M, shape->F, P, shape->D, table, stream) != hipSuccess) {
         return RFSF_E_HIP;
     }
@@ -213,10 +230,10 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
             rfsf::ProfileScope scope(rfsf::kRffIncrements, stream);
             if (rfsf::launch_rff_increments(X + n0 * shape->L * shape->d, W, inv_ls, cnt, shape->L, shape->d,
                                             shape->M, shape->F, shape->rff_bf16 != 0, dphi, stream) != hipSuccess)
-                return RFSF_E_HIP;
+                return fail();
         }
         if (tables_on_side) {           // join: the tables are needed from here on
-            if (hipStreamWaitEvent(stream, side.done, 0) != hipSuccess) return RFSF_E_HIP;
+            if (hipStreamWaitEvent(stream, side.done, 0) != hipSuccess) return fail();
             tables_on_side = false;
         }
         {
@@ -313,6 +330,13 @@ void trp_per_sequence_bytes(const rfsf_ts_shape *s, size_t *incr, size_t *proj)
     *proj = (size_t)s->L * (size_t)s->M * (size_t)s->D * sizeof(float);
 }
 constexpr size_t kTrpFixed = 3 * kAlign;
+// Sequences per launch of the TRP kernels: the scan puts the sequence and the per-level GEMMs put 64-row
+// tiles of the chunk's L*cnt rows on grid.y, which holds at most 65535.
+int64_t trp_chunk_cap(const rfsf_ts_shape *s)
+{
+    const int64_t by_rows = (int64_t)65535 * 64 / s->L;
+    return by_rows < 65535 ? by_rows : 65535;
+}
 }  // namespace
 
 extern "C" int rfsf_trp_workspace_bytes(const rfsf_ts_shape *shape, size_t *recommended_bytes,
@@ -323,7 +347,9 @@ extern "C" int rfsf_trp_workspace_bytes(const rfsf_ts_shape *shape, size_t *reco
     size_t incr, proj;
     trp_per_sequence_bytes(shape, &incr, &proj);
     const size_t per = incr + proj;
+    if (trp_chunk_cap(shape) < 1) return RFSF_E_UNSUPPORTED;     // one sequence alone exceeds the grid
     int64_t chunk = (int64_t)(kChunkBytesTarget / per);
+    if (chunk > trp_chunk_cap(shape)) chunk = trp_chunk_cap(shape);
     if (chunk < 1) chunk = 1;
     if (chunk > shape->N) chunk = shape->N > 0 ? shape->N : 1;
     if (shape->N > 0) {
@@ -349,12 +375,14 @@ extern "C" int rfsf_trp_features(const rfsf_ts_shape *shape, const float *X, con
     if (shape->L == 1)
         return rfsf::launch_fill_trivial(out, shape->N, shape->ld_out, 1 + (int64_t)shape->M * Q, stream) == hipSuccess
                    ? RFSF_OK : RFSF_E_HIP;
+    if (trp_chunk_cap(shape) < 1) return RFSF_E_UNSUPPORTED;
     if (!workspace) return RFSF_E_NULLPTR;
     size_t incr, proj;
     trp_per_sequence_bytes(shape, &incr, &proj);
     if (workspace_bytes < incr + proj + kTrpFixed) return RFSF_E_WORKSPACE_TOO_SMALL;
     int64_t chunk = (int64_t)((workspace_bytes - kTrpFixed) / (incr + proj));
     if (chunk > shape->N) chunk = shape->N;
+    if (chunk > trp_chunk_cap(shape)) chunk = trp_chunk_cap(shape);
     char *base = static_cast<char *>(workspace);
     const size_t mis = (size_t)(reinterpret_cast<uintptr_t>(base) % kAlign);
     float *dphi = reinterpret_cast<float *>(base + (mis ? kAlign - mis : 0));

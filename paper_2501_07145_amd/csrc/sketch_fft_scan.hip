@@ -270,6 +270,18 @@ bool sketch_fft_scan_is_tuned(int M, int F, int D)
     return sketch_fft_scan_lds_bytes(M, F, D) <= kLdsPerCu;
 }
 
+namespace {
+size_t generic_lds_bytes(int D, int order)
+{
+    return sizeof(float2) * (size_t)(2 * D + D / 2 + (order == 2 ? 6 : 2) * (D / 2 + 1));
+}
+}  // namespace
+
+bool sketch_fft_scan_fits(int M, int F, int D, int order)
+{
+    return sketch_fft_scan_is_tuned(M, F, D) || generic_lds_bytes(D, order) <= kLdsPerCu;
+}
+
 size_t sketch_fft_scan_table_bytes(int M, int F, int D)
 {
     TunedGeometry g;
@@ -315,8 +327,8 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
             default: return tuned::dispatch_levels_11(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
         }
     }
-    const size_t lds = sizeof(float2) * (size_t)(2 * D + D / 2 + (order == 2 ? 6 : 2) * (D / 2 + 1));
-    if (lds > kLdsPerCu) return hipErrorInvalidValue;     // order 2 with the longest transform
+    const size_t lds = generic_lds_bytes(D, order);
+    if (lds > kLdsPerCu) return hipErrorInvalidValue;     // the API layer rejects these shapes up front
     static size_t lds_granted = 0;        // per process; raising the limit is idempotent
     if (lds > 64 * 1024 && lds > lds_granted) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(sketch_fft_scan_generic),

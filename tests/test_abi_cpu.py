@@ -45,7 +45,7 @@ def test_strerror_covers_all_codes():
 
 
 def _shape(**kw):
-    base = dict(N=4, L=8, d=3, M=2, F=4, D=8, ld_out=17, rff_bf16=0)
+    base = dict(N=4, L=8, d=3, M=2, F=4, D=8, ld_out=17, rff_bf16=0, order=0)
     base.update(kw)
     return binding._Shape(**base)
 
@@ -93,13 +93,38 @@ def test_bucket_counts_that_are_no_power_of_two_are_accepted_when_small():
         assert (lib.rfsf_ts_workspace_bytes(ctypes.byref(shp), ctypes.byref(rec), ctypes.byref(mn)) == 0) == ok
 
 
+def test_longest_transform_with_order_two_is_refused_before_anything_is_enqueued():
+    # D = 4096 runs the generic kernel, whose LDS need with order 2 exceeds a compute unit's 160 KB
+    lib = binding.load_library()
+    shp = _shape(D=4096, ld_out=1 + 2 * 4096, order=2)
+    assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, 1.0, 256, 256, 1 << 30, None) == -9
+    shp = _shape(D=4096, ld_out=1 + 2 * 4096, order=3)
+    assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, 1.0, 256, 256, 1 << 30, None) == -9
+
+
+def test_trp_chunks_respect_the_grid_limit():
+    # sequences per launch are capped at min(65535, 65535*64/L), whatever the workspace would hold
+    lib = binding.load_library()
+    rec, mn = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    shp = _shape(N=100000, L=32, d=2, M=2, F=4, D=8, ld_out=17)
+    assert lib.rfsf_trp_workspace_bytes(ctypes.byref(shp), ctypes.byref(rec), ctypes.byref(mn)) == 0
+    per = 32 * 2 * 8 * 4 + 32 * 2 * 8 * 4                # increments + projections of one sequence
+    assert (rec.value - 768) // per == 50000             # two equal launches, each below 65535 sequences
+    shp = _shape(N=100000, L=1 << 20, d=2, M=2, F=4, D=8, ld_out=17)
+    assert lib.rfsf_trp_workspace_bytes(ctypes.byref(shp), ctypes.byref(rec), ctypes.byref(mn)) == 0
+    per = (1 << 20) * 2 * 8 * 4 * 2
+    assert (rec.value - 768) // per == 3                  # 65535*64 / 2^20 = 3 sequences per launch
+    shp = _shape(N=4, L=1 << 23, d=2, M=2, F=4, D=8, ld_out=17)    # one sequence alone exceeds the grid
+    assert lib.rfsf_trp_workspace_bytes(ctypes.byref(shp), ctypes.byref(rec), ctypes.byref(mn)) == -9
+
+
 def test_workspace_sizes():
     rec, mn = binding.rfsf_ts_workspace_bytes(1000, 100, 8, 4, 128, 256)
     per_seq = 100 * 4 * 256 * 4 + 4 * 129 * 8           # increment rows + accumulator state
     assert rec - mn == 999 * per_seq                    # the rest is per-call tables and slack
     assert 0 < mn - per_seq < (1 << 20)
     rec_big, mn_big = binding.rfsf_ts_workspace_bytes(50000, 64, 64, 5, 1024, 2048)
-    assert mn_big <= rec_big <= (33 << 30)
+    assert mn_big <= rec_big <= (49 << 30)
 
 
 def test_binding_refuses_host_tensors():

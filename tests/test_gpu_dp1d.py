@@ -28,6 +28,9 @@ def _case(seed, N, L, d, M, F, ls):
     (2, 1, 4, 2, 16),          # no increments
     (2, 2, 64, 6, 40),         # one increment, widest state
     (1, 1000, 2, 8, 9),        # long and narrow
+    (2, 40, 64, 8, 70),        # widest state with eight levels: more than 64 KB of LDS per workgroup
+    (2, 33, 3, 16, 20),        # the largest supported number of levels
+    (1, 20, 40, 13, 300),      # 13 levels on a wide state, two component slabs
 ])
 def test_dp1d_matches_oracle(oracle, N, L, d, M, F):
     X, W, b, ls = _case(N + L + F, N, L, d, M, F, ls=math.sqrt(d))

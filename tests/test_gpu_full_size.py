@@ -10,7 +10,6 @@ import torch
 
 import paper_2501_07145_amd as rfsf
 from paper_2501_07145_amd import workloads as wl
-from tests import pins
 from tests.parity import BF16_BLOCK_TOL, FP32_BLOCK_TOL, GRAM_TOL, block_errors, gram_error
 
 pytestmark = pytest.mark.gpu
@@ -25,23 +24,51 @@ def _features(w, X, tables, workspace):
     return out
 
 
-def _bucket_sum_identity(w, Xs, tables, got_rows, tol):
-    """sum_j Phi_m[j] = sum_{i_1<...<i_m} prod_k u_k[i_k], u_k[t] = sum_a sign_k[a] delta_k[t][a]."""
-    W, hash_, sign = tables
-    delta = pins.rff_increments_numpy(Xs, W, float(np.float32(w.lengthscale)))
-    u = np.einsum("ntma,ma->ntm", delta, sign.astype(np.float64))
-    e = np.zeros((Xs.shape[0], w.M + 1))
-    e[:, 0] = 1.0
-    for t in range(u.shape[1]):
-        for m in range(w.M, 0, -1):
-            e[:, m] += e[:, m - 1] * u[:, t, m - 1]
-    blocks = got_rows[:, 1:].astype(np.float64).reshape(-1, w.M, w.D)
-    scale = np.abs(blocks).sum(axis=2)                # the sum is compared against the block's 1-norm
-    assert np.all(np.abs(blocks.sum(axis=2) - e[:, 1:]) <= tol * scale)
+def _bucket_sum_identity(w, Xs, W, sign, got_rows, tol, batch=64):
+    """sum_j Phi_m[j] = sum_{i_1<...<i_m} prod_k u_k[i_k] with the scalars u_k[t] = sum_a sign_k[a] delta_k[t][a]:
+    summing a level block over its buckets removes the hash. u_k[t] = v_k[t+1] - v_k[t] with
+    v_k[t] = F^-1/2 sum_f (sign_k[f] cos theta_f + sign_k[F+f] sin theta_f), evaluated here in fp64 with torch on
+    the host cores (not the oracle's code)."""
+    ls = float(np.float32(w.lengthscale))
+    Wt = torch.from_numpy(W.astype(np.float64)) / ls
+    sc = torch.from_numpy(sign[:, :w.F].astype(np.float64))
+    ss = torch.from_numpy(sign[:, w.F:].astype(np.float64))
+    worst = 0.0
+    for r0 in range(0, Xs.shape[0], batch):
+        Xb = torch.from_numpy(Xs[r0:r0 + batch].astype(np.float64))
+        theta = torch.einsum("ntc,mcf->ntmf", Xb, Wt)
+        v = ((torch.cos(theta) * sc).sum(dim=3) + (torch.sin(theta) * ss).sum(dim=3)) / math.sqrt(w.F)
+        u = (v[:, 1:] - v[:, :-1]).numpy()
+        e = np.zeros((u.shape[0], w.M + 1))
+        e[:, 0] = 1.0
+        for t in range(u.shape[1]):
+            for m in range(w.M, 0, -1):
+                e[:, m] += e[:, m - 1] * u[:, t, m - 1]
+        blocks = got_rows[r0:r0 + batch, 1:].astype(np.float64).reshape(-1, w.M, w.D)
+        scale = np.abs(blocks).sum(axis=2)                # the sum is compared against the block's 1-norm
+        worst = max(worst, float((np.abs(blocks.sum(axis=2) - e[:, 1:]) / scale).max()))
+    assert worst <= tol, worst
+    return worst
 
 
-@pytest.mark.parametrize("name,n_oracle,n_identity", [("small", 1000, 0), ("medium", 6, 48), ("long", 3, 8),
-                                                      ("large", 6, 48)])
+def _sample_rows(w, rec_bytes, n_oracle, rng):
+    """Rows for the oracle: first, last, the middle pair, both sides of every boundary between the launches the
+    recommended workspace leads to, and random ones up to n_oracle."""
+    if n_oracle >= w.N:
+        return np.arange(w.N), 0
+    _, mn = rfsf.rfsf_ts_workspace_bytes(w.N, w.L, w.d, w.M, w.F, w.D, w.rff_bf16)
+    rec2, mn2 = rfsf.rfsf_ts_workspace_bytes(2, w.L, w.d, w.M, w.F, w.D, w.rff_bf16)
+    chunk = (rec_bytes - mn) // (rec2 - mn2) + 1         # sequences per launch
+    fixed = [0, w.N - 1, w.N // 2 - 1, w.N // 2]
+    for b in range(chunk, w.N, chunk):
+        fixed += [b - 1, b]
+    fixed = np.unique(fixed)
+    extra = rng.integers(0, w.N, size=max(0, n_oracle - len(fixed)))
+    return np.unique(np.concatenate([fixed, extra])), (w.N + chunk - 1) // chunk
+
+
+@pytest.mark.parametrize("name,n_oracle,n_identity", [("small", 1000, 0), ("medium", 64, 512), ("long", 16, 512),
+                                                      ("large", 64, 512)])
 def test_full_size(oracle, name, n_oracle, n_identity):
     w = wl.WORKLOADS[name]
     tables = wl.make_tables(w, 0)
@@ -53,26 +80,26 @@ def test_full_size(oracle, name, n_oracle, n_identity):
     tol = BF16_BLOCK_TOL if w.rff_bf16 else FP32_BLOCK_TOL
 
     rng = np.random.default_rng(5)
-    sel = np.unique(np.concatenate([[0, w.N - 1, w.N // 2 - 1, w.N // 2],
-                                    rng.integers(0, w.N, size=max(0, n_oracle - 4))]))[:max(n_oracle, 4)]
-    if n_oracle >= w.N:
-        sel = np.arange(w.N)
+    sel, launches = _sample_rows(w, rec, n_oracle, rng)
     got = out[torch.from_numpy(sel).cuda()].cpu().numpy()
     want = oracle.features(X[sel], tables[0], tables[1], tables[2], ls, w.D)
     err = block_errors(got, want, w.M, w.D)
-    print(f"{name}: {len(sel)} rows, block errors {err}")
+    print(f"{name}: {len(sel)} oracle rows ({launches} launches), block errors {err}")
     assert np.all(err <= tol)
+    Xm, Wm = X, tables[0]
     if w.rff_bf16:      # kernel error alone: oracle on the operands as multiplied
-        hi = wl.round_to_bf16(X[sel])
-        Xm = (hi + wl.round_to_bf16(X[sel] - hi)).astype(np.float32)
-        same = oracle.features(Xm, wl.round_to_bf16(tables[0]), tables[1], tables[2], ls, w.D)
+        hi = wl.round_to_bf16(X)
+        Xm = (hi + wl.round_to_bf16(X - hi)).astype(np.float32)
+        Wm = wl.round_to_bf16(tables[0])
+        same = oracle.features(Xm[sel], Wm, tables[1], tables[2], ls, w.D)
         err_same = block_errors(got, same, w.M, w.D)
         print(f"{name}: against same-operand oracle {err_same}")
         assert np.all(err_same <= FP32_BLOCK_TOL)
 
-    if n_identity and not w.rff_bf16:
+    if n_identity:      # for the bf16 projection: against the increments of the operands as multiplied
         rows = rng.integers(0, w.N, size=n_identity)
-        _bucket_sum_identity(w, X[rows], tables, out[torch.from_numpy(rows).cuda()].cpu().numpy(), 2e-5)
+        worst = _bucket_sum_identity(w, Xm[rows], Wm, tables[2], out[torch.from_numpy(rows).cuda()].cpu().numpy(), 2e-5)
+        print(f"{name}: bucket-sum identity on {n_identity} rows, worst relative deviation {worst:.2e}")
 
     # Gram: the second batch for the cross Gram, else the batch with itself
     if w.N2:

@@ -57,3 +57,15 @@ def test_trp_chunks_padding_and_errors(oracle):
     with pytest.raises(binding.RfsfTsError) as e:
         _run(X, W, Z, ls, workspace=torch.empty(mn - 1, dtype=torch.uint8, device="cuda"))
     assert e.value.code == -6
+
+
+def test_trp_more_sequences_than_one_launch_may_take(oracle):
+    # 70000 sequences: the scan kernel puts sequences on grid.y (at most 65535), so the call must split
+    # the batch even though the workspace would hold it whole
+    N, L, d, M, F, Q = 70000, 3, 2, 2, 2, 4
+    X, W, Z, ls = _case(11, N, L, d, M, F, Q, 1.0)
+    got = _run(X, W, Z, ls).cpu().numpy()
+    sel = np.r_[0:40, 34990:35010, 65530:65540, N - 40:N]
+    want = oracle.trp_features(X[sel], W, Z, ls)
+    assert np.all(block_errors(got[sel], want, M, Q) <= FP32_BLOCK_TOL)
+    assert np.all(got[:, 0] == 1.0) and np.all(np.isfinite(got))
