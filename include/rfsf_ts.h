@@ -50,7 +50,9 @@ enum {
     RFSF_E_WORKSPACE_TOO_SMALL = -6,/* workspace cannot hold one chunk (see below)        */
     RFSF_E_HIP = -7,                /* a HIP runtime call or kernel launch failed         */
     RFSF_E_BAD_TABLE = -8,          /* hash outside [0, D) or sign not +-1 (validate)     */
-    RFSF_E_UNSUPPORTED = -9         /* valid but outside what the kernels cover           */
+    RFSF_E_UNSUPPORTED = -9,        /* valid but outside what the kernels cover           */
+    RFSF_E_STATIC_SCRATCH_TOO_SMALL = -10 /* rfsf_ts_features_static: one sequence needs  */
+                                    /* more than the built-in scratch                     */
 };
 
 typedef struct {
@@ -115,6 +117,27 @@ int rfsf_ts_features(const rfsf_ts_shape *shape,
                      float *out,
                      void *workspace, size_t workspace_bytes,
                      void *hip_stream);
+
+/*
+ * rfsf_ts_features for callers that cannot allocate device memory: code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments, same results and
+ * same error codes as rfsf_ts_features, minus the workspace: the sketch tables and the increments
+ * of one chunk of sequences live in a 64 MiB array that is part of the library's code object
+ * (one copy per GPU the library runs on, held until the process ends). The call allocates nothing
+ * and creates no streams or events: the tables are built on `hip_stream` itself and the optional
+ * profiling record is not fed. The batch is processed in as many launches as the 64 MiB allow;
+ * a shape whose single sequence (L*M*2F increments plus tables) does not fit returns
+ * RFSF_E_STATIC_SCRATCH_TOO_SMALL with nothing enqueued. The first call on a device looks up the
+ * array's device address once (make that call outside a graph capture). All calls on one GPU share
+ * the array: calls that overlap in time on one GPU (two streams, two threads) race on it; order
+ * them on one stream. Contents between calls are unspecified and nothing relies on them.
+ */
+int rfsf_ts_features_static(const rfsf_ts_shape *shape,
+                            const float *X, const float *W,
+                            const int32_t *hash, const float *sign,
+                            float lengthscale,
+                            float *out,
+                            void *hip_stream);
 
 /*
  * Opt-in device pass that checks the table contents: every hash[m,a] in [0, D) and every

@@ -60,6 +60,8 @@ def load_library():
     lib.rfsf_ts_workspace_bytes.argtypes = [ctypes.POINTER(_Shape), ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.rfsf_ts_features.restype = ctypes.c_int
     lib.rfsf_ts_features.argtypes = [ctypes.POINTER(_Shape), vp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+    lib.rfsf_ts_features_static.restype = ctypes.c_int
+    lib.rfsf_ts_features_static.argtypes = [ctypes.POINTER(_Shape), vp, vp, vp, vp, ctypes.c_float, vp, vp]
     lib.rfsf_ts_validate_tables.restype = ctypes.c_int
     lib.rfsf_ts_validate_tables.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.rfsf_ts_gram.restype = ctypes.c_int
@@ -161,6 +163,28 @@ def rfsf_ts_features(X: torch.Tensor, W: torch.Tensor, hash: torch.Tensor, sign:
     _check(lib.rfsf_ts_features(ctypes.byref(shp), X.data_ptr(), W.data_ptr(), hash.data_ptr(),
                                 sign.data_ptr(), float(lengthscale), out.data_ptr(),
                                 workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return out[:, :ncols]
+
+
+def rfsf_ts_features_static(X: torch.Tensor, W: torch.Tensor, hash: torch.Tensor, sign: torch.Tensor,
+                            lengthscale: float, D: int, out: torch.Tensor, rff_bf16: bool = False,
+                            stream: Optional[torch.cuda.Stream] = None, order: int = 1) -> torch.Tensor:
+    """rfsf_ts_features through the entry point that allocates nothing: the caller passes `out`, the
+    library uses its built-in 64 MiB scratch. Nothing is allocated here either."""
+    lib = load_library()
+    X = _dev(X, torch.float32, "X")
+    W = _dev(W, torch.float32, "W")
+    hash = _dev(hash, torch.int32, "hash")
+    sign = _dev(sign, torch.float32, "sign")
+    N, M = X.shape[0], W.shape[0]
+    ncols = 1 + M * int(D)
+    if out.dim() != 2 or out.dtype != torch.float32 or not out.is_cuda or out.shape[0] != N or \
+            out.shape[1] < ncols or (out.shape[1] > 0 and out.stride(1) != 1):
+        raise ValueError("out must be float32 [N, >= 1+M*D] on the device with unit column stride")
+    ld_out = out.stride(0) if N > 1 else max(out.stride(0), out.shape[1])
+    shp = _shape_of(X, W, hash, D, ld_out, rff_bf16, order)
+    _check(lib.rfsf_ts_features_static(ctypes.byref(shp), X.data_ptr(), W.data_ptr(), hash.data_ptr(),
+                                       sign.data_ptr(), float(lengthscale), out.data_ptr(), _stream_ptr(stream)))
     return out[:, :ncols]
 
 

@@ -58,7 +58,7 @@ hipError_t launch_validate_tables(const int32_t *hash, const float *sign, int64_
 // constructed and a stop event when destroyed, if profiling is on.
 enum KernelClass { kRffIncrements = 0, kSketchFftScan = 1, kGram = 2, kNormalize = 3, kDp1d = 4, kTrpProject = 5, kTrpScan = 6, kNumKernelClasses = 7 };
 struct ProfileScope {
-    ProfileScope(KernelClass k, hipStream_t stream);
+    ProfileScope(KernelClass k, hipStream_t stream, bool allowed = true);
     ~ProfileScope();
     int slot;
     hipStream_t stream;

@@ -12,9 +12,9 @@ bool g_profile_on = false;
 std::vector<TimedLaunch> g_launches;
 }  // namespace
 
-ProfileScope::ProfileScope(KernelClass k, hipStream_t s) : slot(-1), stream(s)
+ProfileScope::ProfileScope(KernelClass k, hipStream_t s, bool allowed) : slot(-1), stream(s)
 {
-    if (!g_profile_on) return;
+    if (!g_profile_on || !allowed) return;
     TimedLaunch t{nullptr, nullptr, k};
     if (hipEventCreate(&t.start) != hipSuccess) return;
     if (hipEventCreate(&t.stop) != hipSuccess) { (void)hipEventDestroy(t.start); return; }
@@ -137,6 +137,8 @@ extern "C" const char *rfsf_ts_strerror(int code)
         case RFSF_E_HIP: return "HIP runtime error";
         case RFSF_E_BAD_TABLE: return "hash outside [0, D) or sign not +-1";
         case RFSF_E_UNSUPPORTED: return "configuration not supported by this build";
+        case RFSF_E_STATIC_SCRATCH_TOO_SMALL:
+            return "one sequence needs more than the 64 MiB built-in scratch: use rfsf_ts_features with a workspace";
         default: return "unknown rfsf_ts error code";
     }
 }
@@ -162,9 +164,13 @@ extern "C" int rfsf_ts_workspace_bytes(const rfsf_ts_shape *shape, size_t *recom
     return RFSF_OK;
 }
 
-extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, const float *W,
-                                const int32_t *hash, const float *sign, float lengthscale, float *out,
-                                void *workspace, size_t workspace_bytes, void *hip_stream)
+namespace {
+// Body of rfsf_ts_features. `may_create` = false keeps the call free of anything that creates runtime
+// objects: the tables are then built on the caller's stream (no library-owned stream or events) and no
+// profiling events are recorded.
+int features_impl(const rfsf_ts_shape *shape, const float *X, const float *W, const int32_t *hash,
+                  const float *sign, float lengthscale, float *out, void *workspace, size_t workspace_bytes,
+                  void *hip_stream, bool may_create)
 {
     int rc = check_shape(shape);
     if (rc != RFSF_OK) return rc;
@@ -200,7 +206,8 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
     float *dphi = reinterpret_cast<float *>(p_incr);
     float *state = reinterpret_cast<float *>(p_state);
     uint32_t *table = reinterpret_cast<uint32_t *>(p_table);
-    SideStream &side = side_stream();
+    static SideStream no_side;
+    SideStream &side = may_create ? side_stream() : no_side;
     bool tables_on_side = false;
     // Error return after the fork: the caller's stream first waits for whatever the side stream still does
     // (the table build writes the workspace), so that the workspace is quiet once `stream` has drained.
@@ -227,7 +234,7 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
     for (int64_t n0 = 0; n0 < shape->N; n0 += chunk) {
         const int64_t cnt = shape->N - n0 < chunk ? shape->N - n0 : chunk;
         {
-            rfsf::ProfileScope scope(rfsf::kRffIncrements, stream);
+            rfsf::ProfileScope scope(rfsf::kRffIncrements, stream, may_create);
             if (rfsf::launch_rff_increments(X + n0 * shape->L * shape->d, W, inv_ls, cnt, shape->L, shape->d,
                                             shape->M, shape->F, shape->rff_bf16 != 0, dphi, stream) != hipSuccess)
                 return fail();
@@ -237,13 +244,61 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
             tables_on_side = false;
         }
         {
-            rfsf::ProfileScope scope(rfsf::kSketchFftScan, stream);
+            rfsf::ProfileScope scope(rfsf::kSketchFftScan, stream, may_create);
             if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, table, cnt, shape->L, shape->M, shape->F, P, shape->D,
                                              shape->order == 2 ? 2 : 1, out + n0 * shape->ld_out, shape->ld_out, state, stream) != hipSuccess)
                 return RFSF_E_HIP;
         }
     }
     return RFSF_OK;
+}
+
+// Scratch of the entry point that allocates nothing: one array per GPU, part of the library's code object.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+// Device address of `scratch` on the current device, resolved once per device (each GPU holds its own copy
+// at its own address); nullptr if the lookup fails.
+void *static_scratch_address()
+{
+    static void *address[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    if (!address[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        address[dev] = ptr;
+    }
+    return address[dev];
+}
+}  // namespace
+
+extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, const float *W,
+                                const int32_t *hash, const float *sign, float lengthscale, float *out,
+                                void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return features_impl(shape, X, W, hash, sign, lengthscale, out, workspace, workspace_bytes, hip_stream, true);
+}
+
+extern "C" int rfsf_ts_features_static(const rfsf_ts_shape *shape, const float *X, const float *W,
+                                       const int32_t *hash, const float *sign, float lengthscale, float *out,
+                                       void *hip_stream)
+{
+    const int rc = check_shape(shape);
+    if (rc != RFSF_OK) return rc;
+    if (shape->N > 0 && shape->L > 1) {      // one sequence (increments + state) plus the tables must fit
+        size_t incr, state;
+        per_sequence_bytes(shape, &incr, &state);
+        if (incr + state > kStaticScratchBytes || fixed_bytes(shape) > kStaticScratchBytes - (incr + state))
+            return RFSF_E_STATIC_SCRATCH_TOO_SMALL;
+    }
+    void *ptr = static_scratch_address();
+    if (!ptr) return RFSF_E_HIP;
+    return features_impl(shape, X, W, hash, sign, lengthscale, out, ptr, kStaticScratchBytes, hip_stream, false);
 }
 
 extern "C" int rfsf_ts_validate_tables(const int32_t *hash, const float *sign, int32_t M, int32_t F,

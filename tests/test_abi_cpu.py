@@ -36,11 +36,11 @@ def test_every_declared_symbol_is_exported():
 def test_strerror_covers_all_codes():
     lib = binding.load_library()
     seen = set()
-    for code in range(0, -10, -1):
+    for code in range(0, -11, -1):
         s = lib.rfsf_ts_strerror(code).decode()
         assert s and "unknown" not in s
         seen.add(s)
-    assert len(seen) == 10
+    assert len(seen) == 11
     assert "unknown" in lib.rfsf_ts_strerror(-99).decode()
 
 
