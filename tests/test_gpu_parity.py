@@ -215,7 +215,7 @@ def test_results_are_bit_reproducible():
     assert torch.equal(Ka, Kb)
 
 
-@pytest.mark.parametrize("N,C", [(2100, 517), (2049, 64), (4500, 100), (1000, 1025)])
+@pytest.mark.parametrize("N,C", [(2100, 517), (2049, 64), (4500, 100), (1000, 1025), (4501, 70), (4222, 33)])
 def test_symmetric_gram_path(oracle, N, C):
     """K = Phi Phi^T with one operand: only the upper triangle is computed, the rest mirrored."""
     rng = np.random.default_rng(N + C)
