@@ -12,8 +12,12 @@ namespace rfsf {
 // Element (g, m, a) sits at ((g * M + m) * 2F + a).
 
 // Steps 1-2: random Fourier features of every time point and their time increments
-// for `n_seq` sequences starting at X (already offset to the chunk).
-hipError_t launch_rff_increments(const float *X, const float *W, float inv_lengthscale,
+// for `n_seq` sequences starting at X (already offset to the chunk), halved.
+// sign == nullptr: row layout, element (g, m, a) of row g = n * L + t at ((g * M + m) * 2F + a), no signs.
+// sign != nullptr ([M, 2F], the CountSketch signs): pair layout with the signs applied. With Lp = L rounded up
+// to even, increment k = n * Lp + t of coordinate a sits at ((((k / 2) * M + m) * 2F + a) * 2 + k % 2): the
+// two increments of a pair of consecutive time steps are one float2. n_seq * Lp * M * 2F floats in all.
+hipError_t launch_rff_increments(const float *X, const float *W, const float *sign, float inv_lengthscale,
                                  int64_t n_seq, int64_t L, int d, int M, int F, bool bf16,
                                  float *dphi, hipStream_t stream);
 

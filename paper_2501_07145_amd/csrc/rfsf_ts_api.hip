@@ -72,7 +72,8 @@ int check_shape(const rfsf_ts_shape *s)
 // Bytes of workspace one sequence needs: its increment rows plus its accumulator state.
 void per_sequence_bytes(const rfsf_ts_shape *s, size_t *incr, size_t *state)
 {
-    *incr = (size_t)s->L * (size_t)s->M * 2u * (size_t)s->F * sizeof(float);
+    // rows of increments per sequence: L in the row layout, L rounded up to even in the pair layout
+    *incr = (size_t)((s->L + 1) & ~(int64_t)1) * (size_t)s->M * 2u * (size_t)s->F * sizeof(float);
     *state = rfsf::sketch_fft_scan_state_bytes(1, s->M, transform_length(s->M, s->D));
 }
 
@@ -231,11 +232,14 @@ int features_impl(const rfsf_ts_shape *shape, const float *X, const float *W, co
     }
 
     const float inv_ls = 1.0f / lengthscale;
+    // the tuned consumer takes the increments in the pair layout with the signs applied, the generic one in
+    // the row layout without
+    const float *producer_sign = rfsf::sketch_fft_scan_is_tuned(shape->M, shape->F, P) ? sign : nullptr;
     for (int64_t n0 = 0; n0 < shape->N; n0 += chunk) {
         const int64_t cnt = shape->N - n0 < chunk ? shape->N - n0 : chunk;
         {
             rfsf::ProfileScope scope(rfsf::kRffIncrements, stream, may_create);
-            if (rfsf::launch_rff_increments(X + n0 * shape->L * shape->d, W, inv_ls, cnt, shape->L, shape->d,
+            if (rfsf::launch_rff_increments(X + n0 * shape->L * shape->d, W, producer_sign, inv_ls, cnt, shape->L, shape->d,
                                             shape->M, shape->F, shape->rff_bf16 != 0, dphi, stream) != hipSuccess)
                 return fail();
         }
@@ -449,7 +453,7 @@ extern "C" int rfsf_trp_features(const rfsf_ts_shape *shape, const float *X, con
         const int64_t cnt = shape->N - n0 < chunk ? shape->N - n0 : chunk;
         {
             rfsf::ProfileScope scope(rfsf::kRffIncrements, stream);
-            if (rfsf::launch_rff_increments(X + n0 * shape->L * shape->d, W, inv_ls, cnt, shape->L, shape->d,
+            if (rfsf::launch_rff_increments(X + n0 * shape->L * shape->d, W, nullptr, inv_ls, cnt, shape->L, shape->d,
                                             shape->M, shape->F, shape->rff_bf16 != 0, dphi, stream) != hipSuccess)
                 return RFSF_E_HIP;
         }

@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
 constexpr int kTableThreads = 1024;
 
 __global__ __launch_bounds__(1024) void build_tables_kernel(
-    const int32_t *__restrict__ hash, const float *__restrict__ sign, int twoF, int D, int Dout, int G, int LOADB,
+    const int32_t *__restrict__ hash, const float *__restrict__ sign, int twoF, int D, int Dout, int G,
     int PD, uint32_t *__restrict__ table)
 {
     extern __shared__ __attribute__((aligned(16))) int table_scratch[];
@@ -156,8 +156,9 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(
     int *h = table_scratch, *rk = h + tf4, *cls = rk + tf4, *src0 = cls + tf4 + 4, *src1 = src0 + D;
     __shared__ int max_rank, n_rounds;
     const int m = blockIdx.x, tid = threadIdx.x;
-    const tuned::TableLayout tl = tuned::table_layout(D, G, LOADB, twoF);
+    const tuned::TableLayout tl = tuned::table_layout(D, G, twoF);
     uint32_t *tab = table + (int64_t)m * tl.words;
+    (void)sign;                           // applied by the producing kernel
     const uint32_t zero_off = (uint32_t)tuned::zero_slot(PD, twoF) * 8u;
 
     for (int a = tid; a < twoF; a += kTableThreads) h[a] = ((hash[(int64_t)m * twoF + a] % Dout) + Dout) % Dout;
@@ -195,15 +196,6 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(
         const uint32_t s0 = src0[e] >= 0 ? (uint32_t)src0[e] * 8u : zero_off;
         const uint32_t s1 = src1[e] >= 0 ? (uint32_t)src1[e] * 8u : zero_off;
         tab[tl.gather + e] = s0 | (s1 << 16);
-    }
-    for (int i = tid; i < tl.nbatch * 64; i += kTableThreads) {
-        const int bi = i >> 6, lane = i & 63;
-        uint32_t w = 0;
-        for (int b = 0; b < LOADB; ++b) {
-            const int a = bi * 64 * LOADB + 64 * b + lane;
-            if (a < twoF && (__float_as_uint(sign[(int64_t)m * twoF + a]) >> 31)) w |= 1u << b;
-        }
-        tab[tl.signs + i] = w;
     }
     __syncthreads();                      // padding entries are in place before the real ones land
     for (int a = tid; a < twoF; a += kTableThreads) {
@@ -243,11 +235,11 @@ size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D)
 }
 
 namespace {
-struct TunedGeometry { int G /* entries per fold round */, LOADB, PD, FPW, NTWL; };
+struct TunedGeometry { int G /* entries per fold round */, PD, FPW, NTWL; };
 bool tuned_geometry(int D, TunedGeometry *g)
 {
     switch (D) {
-#define RFSF_GEOM(L2) case 1 << L2: *g = {tuned::Plan<L2>::GF, tuned::Plan<L2>::LOADB, tuned::Plan<L2>::PD, tuned::Plan<L2>::FPW, tuned::Plan<L2>::NTWL}; return true;
+#define RFSF_GEOM(L2) case 1 << L2: *g = {tuned::Plan<L2>::GF, tuned::Plan<L2>::PD, tuned::Plan<L2>::FPW, tuned::Plan<L2>::NTWL}; return true;
         RFSF_GEOM(6) RFSF_GEOM(7) RFSF_GEOM(8) RFSF_GEOM(9) RFSF_GEOM(10) RFSF_GEOM(11)
 #undef RFSF_GEOM
         default: return false;
@@ -286,7 +278,7 @@ size_t sketch_fft_scan_table_bytes(int M, int F, int D)
 {
     TunedGeometry g;
     if (!sketch_fft_scan_is_tuned(M, F, D) || !tuned_geometry(D, &g)) return 0;
-    return sizeof(uint32_t) * (size_t)M * tuned::table_layout(D, g.G, g.LOADB, 2 * F).words;
+    return sizeof(uint32_t) * (size_t)M * tuned::table_layout(D, g.G, 2 * F).words;
 }
 
 hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int F, int D, int Dout,
@@ -306,7 +298,7 @@ hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int
         }
     }
     hipLaunchKernelGGL(build_tables_kernel, dim3((unsigned)M), dim3(kTableThreads), lds, stream, hash, sign, twoF, D, Dout,
-                       g.G, g.LOADB, g.PD, table);
+                       g.G, g.PD, table);
     return hipGetLastError();
 }
 

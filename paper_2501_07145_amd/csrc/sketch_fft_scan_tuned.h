@@ -4,9 +4,12 @@
 // Work decomposition (one workgroup per sequence, M wavefronts, wavefront m owns level m; for D = 2048
 // two wavefronts share a level and its single transform, see Plan::WPL):
 //   per iteration every wavefront handles FPW pairs of consecutive time steps of its level:
-//     1. CountSketch as a gather. The signed increments of the 2*FPW time steps are written to
-//        LDS in their natural order (step 2k -> real part, step 2k+1 -> imaginary part of the
-//        float2 of coordinate a, one staging area per pair). A table built once per call lists,
+//     1. CountSketch as a gather. The signed increments of the 2*FPW time steps arrive in LDS in
+//        their natural order (step 2k -> real part, step 2k+1 -> imaginary part of the float2 of
+//        coordinate a, one staging area per pair): the producing kernel stores them in exactly this
+//        form, signs applied, and they are loaded from global memory straight into LDS
+//        (global_load_lds_dwordx4: 16 bytes per lane at LDS base + 16 * lane), without passing
+//        through registers and without LDS-write instructions. A table built once per call lists,
 //        for every bucket, the first two coordinates that hash to it; the few coordinates that
 //        are third or later in their bucket are first folded into the bucket's first coordinate
 //        by conflict-free read-add-write rounds (one round per rank, so no two lanes of a round
@@ -27,8 +30,8 @@
 //   faster: the pace is set by the instruction streams of the resident workgroups, not by the load
 //   latency of one of them. What did pay off every time was more resident wavefronts.)
 //
-// The increments arrive pre-multiplied by 1/2 (done by the producing kernel), which is the
-// factor of the two-for-one separation  C0 = (Z[f] + conj Z[D-f]) / 2,  C1 = (Z[f] - conj Z[D-f]) / 2i.
+// The increments arrive pre-multiplied by 1/2 and by their CountSketch sign (done by the producing
+// kernel); 1/2 is the factor of the two-for-one separation  C0 = (Z[f] + conj Z[D-f]) / 2,  C1 = (Z[f] - conj Z[D-f]) / 2i.
 #pragma once
 
 #include "rfsf_internal.h"
@@ -51,7 +54,6 @@ struct Plan {
     static constexpr int FPW = G > 64 ? 1 : 64 / G;   // transforms per wavefront (per level when WPL > 1)
     static constexpr int GF = G > 64 ? 64 : G;  // entries per fold round (the first wavefront of a level folds)
     static constexpr int PD = D + D / 16;       // padded transform length in float2
-    static constexpr int LOADB = FPW >= 16 ? 1 : 16 / FPW;   // 64-coordinate groups fetched per batch
     static constexpr int NP = LOG2D <= 4 ? 1 : (LOG2D <= 8 ? 2 : 3);
     static constexpr int radix(int p)
     {
@@ -90,30 +92,27 @@ struct Plan {
     static constexpr int roff(int q) { return G >= 16 ? q * (G + G / 16) : pad(G * q); }
 };
 
-// Geometry of one LDS slot (float2 units): [0, ZS) data -- the staging area uses [0, 2F), the
-// transform [0, PD) --, [ZS] a float2 that is always zero (source of buckets without a first or
-// second coordinate).
-__host__ __device__ constexpr int zero_slot(int PD, int twoF) { return PD > twoF ? PD : twoF; }
+// Geometry of one LDS slot (float2 units): [0, ZS) data -- the staging area uses [0, 2F) and, because a
+// direct load always deposits 128 coordinates, junk up to the next multiple of 128; the transform uses
+// [0, PD) --, [ZS] a float2 that is always zero (source of buckets without a first or second coordinate).
+__host__ __device__ constexpr int staged(int twoF) { return (twoF + 127) & ~127; }
+__host__ __device__ constexpr int zero_slot(int PD, int twoF) { return PD > staged(twoF) ? PD : staged(twoF); }
 __host__ __device__ constexpr int slot_stride(int PD, int twoF) { return (zero_slot(PD, twoF) + 2) & ~1; }
 
 // Per-level table built once per call (uint32 words):
 //   [0]                 NG, number of fold rounds
 //   [64, 64 + D)        gather words: low 16 bits byte offset of the bucket's first coordinate in the
 //                       staging area, high 16 bits of its second one (zero float2 if there is none)
-//   [.., + NBATCH*64)   sign words: bit b of word (batch, lane) is the sign of coordinate
-//                       batch*64*LOADB + 64*b + lane
 //   [.., + 2F*G)        fold entries, G per round: low 16 bits byte offset of the coordinate to fold,
 //                       high 16 bits byte offset of the first coordinate of its bucket (0xffff: padding)
 struct TableLayout {
-    int nbatch, gather, signs, fold, words;
+    int gather, fold, words;
 };
-__host__ __device__ inline TableLayout table_layout(int D, int G, int LOADB, int twoF)
+__host__ __device__ inline TableLayout table_layout(int D, int G, int twoF)
 {
     TableLayout t;
-    t.nbatch = (twoF + 64 * LOADB - 1) / (64 * LOADB);
     t.gather = 64;
-    t.signs = t.gather + D;
-    t.fold = t.signs + t.nbatch * 64;
+    t.fold = t.gather + D;
     t.words = (t.fold + twoF * G + 63) & ~63;
     return t;
 }
@@ -331,11 +330,15 @@ __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
     float2 *my_slot = wave_lds + slot_id * PS;
     char *my_slot_bytes = reinterpret_cast<char *>(my_slot);
     const int64_t n = blockIdx.x, T = L - 1;
-    const int64_t rf = (int64_t)M * twoF;
-    const float *seq = dphi + n * L * rf + (int64_t)m * twoF;   // row k of this level: seq + k * rf
-    const TableLayout tl = table_layout(D, P::GF, P::LOADB, twoF);
+    const int64_t pairs = (T + 1) / 2;
+    // pair p of this level: 2F float2 at seq + p * pf (pair layout of the producing kernel, Lp / 2 pair slots
+    // per sequence with Lp = L rounded up to even)
+    const int64_t pf = (int64_t)M * 2 * twoF;
+    const float *seq = dphi + n * ((L + 1) / 2) * pf + (int64_t)m * 2 * twoF;
+    const TableLayout tl = table_layout(D, P::GF, twoF);
     const uint32_t *tab = table + (int64_t)m * tl.words;
     const int NG = (int)tab[0];
+    const int nload = staged(twoF) / 128;                    // direct loads per pair, 128 coordinates each
 
     WaveFft<P> fft;
     fft.init(lg, twl_table);
@@ -348,49 +351,23 @@ __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
 #pragma unroll
         for (int l = 0; l < M; ++l) A[b][l] = make_float2(0.f, 0.f);
 
-    // Rows 2*(pair0+s) and 2*(pair0+s)+1 of this level, coordinates a0 + 64*b + lane, as (re, im).
-    // Row addresses are wavefront-uniform (scalar base) and the coordinate offset is lane + constant,
-    // so a load is one instruction with an immediate offset. Rows beyond the last increment are
-    // redirected to the last one and zeroed; coordinates beyond 2F read the following floats of the
-    // workspace (which is padded at its end for this) and are dropped when staging.
-    float2 val[P::LOADB][P::FPW];
-    auto fetch = [&](int64_t pair0, int a0) {
+    // Staging: pair pair0 + s goes to slot s of the level, 128 coordinates (1 KB) per instruction, lane i
+    // supplying coordinates 2i and 2i+1. A level's wavefronts take the instructions in turn. Pairs beyond the
+    // last one (final iteration only) are redirected to the last pair and ignored later; coordinates beyond 2F
+    // read the following floats of the workspace (which is padded at its end for this) and land in the unused
+    // part of the staging area.
+    auto stage_direct = [&](int64_t pair0) {
 #pragma unroll
         for (int s = 0; s < P::FPW; ++s) {
-            const int64_t k0 = 2 * (pair0 + s);
-            const int64_t kk0 = k0 < T ? k0 : T - 1, kk1 = k0 + 1 < T ? k0 + 1 : T - 1;
-            const float *r0 = seq + kk0 * rf + a0, *r1 = seq + kk1 * rf + a0;
-#pragma unroll
-            for (int b = 0; b < P::LOADB; ++b) val[b][s] = make_float2(r0[lane + 64 * b], r1[lane + 64 * b]);
-            if (k0 + 1 >= T) {                      // wavefront-uniform: only in the last iteration
-#pragma unroll
-                for (int b = 0; b < P::LOADB; ++b) {
-                    val[b][s].y = 0.f;
-                    if (k0 >= T) val[b][s].x = 0.f;
-                }
-            }
-        }
-    };
-    // Signs applied, values written to the staging areas (natural coordinate order).
-    auto stage = [&](int a0, uint32_t sign_word) {
-        // wavefront-uniform: no lane runs past 2F (measured: pays off when a wavefront stages several
-        // pairs, costs 10 % when it stages one, so it is used for FPW > 1 only)
-        const bool full = P::FPW > 1 && a0 + 64 * P::LOADB <= twoF;
-#pragma unroll
-        for (int s = 0; s < P::FPW; ++s) {
-            float2 *dst = wave_lds + s * PS + a0 + lane;
-#pragma unroll
-            for (int b = 0; b < P::LOADB; ++b) {
-                const uint32_t sgn = (sign_word << (31 - b)) & 0x80000000u;
-                const float2 x = make_float2(__uint_as_float(__float_as_uint(val[b][s].x) ^ sgn),
-                                             __uint_as_float(__float_as_uint(val[b][s].y) ^ sgn));
-                if (full) dst[64 * b] = x;
-                else if (a0 + 64 * b + lane < twoF) dst[64 * b] = x;
-            }
+            const int64_t p = pair0 + s < pairs ? pair0 + s : pairs - 1;
+            const float *src = seq + p * pf + 4 * lane;
+            float2 *dst = wave_lds + s * PS;
+            for (int j = sub; j < nload; j += P::WPL)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + 256 * j),
+                                                 (__attribute__((address_space(3))) void *)(dst + 128 * j), 16, 0, 0);
         }
     };
 
-    const int64_t pairs = (T + 1) / 2;
     for (int64_t pair0 = 0; pair0 < pairs; pair0 += P::FPW) {
         // Tables of this level. They are the same every iteration and stay in L1/L2; the pointer is
         // laundered so that the compiler reloads them here instead of keeping ~90 loop-invariant
@@ -402,18 +379,15 @@ __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
         for (int q = 0; q < P::R; ++q) gw[q] = tabi[tl.gather + lg + P::G * q];
 #pragma unroll
         for (int g = 0; g < kFoldInRegs; ++g) fw[g] = g < NG ? tabi[tl.fold + g * P::GF + (lg % P::GF)] : kFoldPad << 16;
-        // a level's wavefronts take the 64*LOADB-coordinate batches in turn
-        const uint32_t sw0 = tabi[tl.signs + sub * 64 + lane];
 
-        // 1a. staging, one batch of 64*LOADB coordinates at a time
-        if (sub < tl.nbatch) {
-            fetch(pair0, sub * 64 * P::LOADB);
-            stage(sub * 64 * P::LOADB, sw0);
-        }
-        for (int bi = sub + P::WPL; bi < tl.nbatch; bi += P::WPL) {
-            const int a0 = bi * 64 * P::LOADB;
-            fetch(pair0, a0);
-            stage(a0, tabi[tl.signs + bi * 64 + lane]);
+        // 1a. staging
+        stage_direct(pair0);
+        __builtin_amdgcn_s_waitcnt(0x0f70);                 // vmcnt(0): the direct loads have landed
+        if ((T & 1) && pair0 + P::FPW >= pairs) {
+            // odd number of increments, last pair: its second step does not exist; what the producer left in
+            // its place (the increment across the sequence boundary) is cleared so that it cannot touch the result
+            float2 *st = wave_lds + (int)(pairs - 1 - pair0) * PS;
+            for (int a = sub * 64 + lane; a < twoF; a += 64 * P::WPL) st[a].y = 0.f;
         }
         transform_fence<P>();
         // 1b. fold the third and later coordinates of a bucket into its first one, one rank per round
@@ -457,6 +431,7 @@ __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
 #pragma unroll
         for (int s = 0; s < P::FPW; ++s) {
             const bool second_step = 2 * (pair0 + s) + 1 < T;      // wavefront-uniform
+            if (pair0 + s >= pairs) continue;                       // slot without a pair (last iteration only)
 #pragma unroll
             for (int b = 0; b < BPT; ++b) {
                 const int f = tid_here + NT * b;
