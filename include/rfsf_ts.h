@@ -62,8 +62,10 @@ typedef struct {
     int32_t rff_bf16;    /* 0: fp32 projection. 1: W rounded to bf16, X split into two     */
                          /* bf16 terms, products accumulated in fp32 on the matrix cores   */
     int32_t order;       /* signature order p: 0 or 1 -> strictly increasing time tuples    */
-                         /* (the default); 2 -> a time step may be used twice in a row with  */
-                         /* weight 1/2 (Sec. 2.1, Sec. 3.5 eq. (ts_rec), q = 2). Larger: no. */
+                         /* (the default); 2, 3 -> a time step may be used up to p times in  */
+                         /* a row, q equal indices weighted 1/q! (Sec. 2.1, Sec. 3.5 eq.     */
+                         /* (ts_rec), the terms q <= p). 3 needs a power-of-two D in         */
+                         /* [64, 2048] (or a transform of that length), M <= 8. Larger: no.  */
 } rfsf_ts_shape;
 
 /* Human-readable text for a return code. Never NULL. Host pointer, static storage. */
@@ -117,6 +119,24 @@ int rfsf_ts_features(const rfsf_ts_shape *shape,
                      float *out,
                      void *workspace, size_t workspace_bytes,
                      void *hip_stream);
+
+/*
+ * rfsf_ts_features for a batch of sequences of different lengths (appendix, ksig.preprocessing: the package
+ * takes variable-length input and tabulates it to a common length). X holds N sequences padded to L points
+ * each; lengths[n] in [1, L] is the number of points of sequence n that exist, the content of X beyond them
+ * is never used for the result. Row n of `out` equals what rfsf_ts_features gives for X[n, 0 .. lengths[n]-1, :]
+ * alone (lengths[n] = 1: (1, 0, ..., 0)).
+ *   lengths [N] int64 device pointer, or NULL for "all L" (then identical to rfsf_ts_features). Values outside
+ *   [1, L] are clamped into it (they are never used as addresses).
+ * Everything else as for rfsf_ts_features, including the workspace sizes.
+ */
+int rfsf_ts_features_ragged(const rfsf_ts_shape *shape,
+                            const float *X, const int64_t *lengths, const float *W,
+                            const int32_t *hash, const float *sign,
+                            float lengthscale,
+                            float *out,
+                            void *workspace, size_t workspace_bytes,
+                            void *hip_stream);
 
 /*
  * rfsf_ts_features for callers that cannot allocate device memory: code running under HIP graph

@@ -98,6 +98,22 @@ def features(X, W, hash_, sign, lengthscale: float, D: int, order: int = 1) -> n
     return out
 
 
+def features_ragged(X, lengths, W, hash_, sign, lengthscale: float, D: int, order: int = 1) -> np.ndarray:
+    """Variable-length batch (appendix, ksig.preprocessing: sequences of different lengths): X[N, L, d] padded,
+    lengths[n] in [1, L] points of sequence n exist. Row n is the feature map of X[n, :lengths[n]] alone: the
+    routine above is called once per distinct length on the sequences of that length, truncated."""
+    X = _f32(X)
+    lengths = np.asarray(lengths, dtype=np.int64)
+    if X.ndim != 3 or lengths.shape != (X.shape[0],) or np.any(lengths < 1) or np.any(lengths > X.shape[1]):
+        raise ValueError("expected X[N,L,d] and lengths[N] in [1, L]")
+    M = np.asarray(W).shape[0]
+    out = np.empty((X.shape[0], 1 + M * int(D)), dtype=np.float64)
+    for ell in np.unique(lengths):
+        idx = np.nonzero(lengths == ell)[0]
+        out[idx] = features(X[idx, :int(ell)], W, hash_, sign, lengthscale, D, order)
+    return out
+
+
 def increments(X, W, lengthscale: float) -> np.ndarray:
     """float64 [N, T, M, 2F]: time increments of the per-level random Fourier features."""
     X, W = _f32(X), _f32(W)

@@ -60,6 +60,8 @@ def load_library():
     lib.rfsf_ts_workspace_bytes.argtypes = [ctypes.POINTER(_Shape), ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.rfsf_ts_features.restype = ctypes.c_int
     lib.rfsf_ts_features.argtypes = [ctypes.POINTER(_Shape), vp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+    lib.rfsf_ts_features_ragged.restype = ctypes.c_int
+    lib.rfsf_ts_features_ragged.argtypes = [ctypes.POINTER(_Shape), vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
     lib.rfsf_ts_features_static.restype = ctypes.c_int
     lib.rfsf_ts_features_static.argtypes = [ctypes.POINTER(_Shape), vp, vp, vp, vp, ctypes.c_float, vp, vp]
     lib.rfsf_ts_validate_tables.restype = ctypes.c_int
@@ -136,11 +138,13 @@ def feature_row_stride(M: int, D: int) -> int:
 def rfsf_ts_features(X: torch.Tensor, W: torch.Tensor, hash: torch.Tensor, sign: torch.Tensor,
                      lengthscale: float, D: int, out: Optional[torch.Tensor] = None,
                      workspace: Optional[torch.Tensor] = None, rff_bf16: bool = False,
-                     stream: Optional[torch.cuda.Stream] = None, order: int = 1) -> torch.Tensor:
+                     stream: Optional[torch.cuda.Stream] = None, order: int = 1,
+                     lengths: Optional[torch.Tensor] = None) -> torch.Tensor:
     """RFSF-TS features of a batch: returns a [N, 1 + M*D] float32 view (row stride
     feature_row_stride(M, D) when allocated here). `out` may be any 2-D float32 device
     tensor with unit column stride and at least 1 + M*D columns; `workspace` any
-    contiguous uint8 device tensor of at least the minimum size."""
+    contiguous uint8 device tensor of at least the minimum size. `lengths` (int64 [N] on the
+    device) gives each sequence's own number of points when X is a padded variable-length batch."""
     lib = load_library()
     X = _dev(X, torch.float32, "X")
     W = _dev(W, torch.float32, "W")
@@ -160,6 +164,14 @@ def rfsf_ts_features(X: torch.Tensor, W: torch.Tensor, hash: torch.Tensor, sign:
         rec, _ = rfsf_ts_workspace_bytes(shp.N, shp.L, shp.d, shp.M, shp.F, shp.D, rff_bf16)
         workspace = _empty_on(stream, rec, dtype=torch.uint8, device=X.device)
     workspace = _dev(workspace, torch.uint8, "workspace")
+    if lengths is not None:
+        lengths = _dev(lengths, torch.int64, "lengths")
+        if tuple(lengths.shape) != (N,):
+            raise ValueError("lengths must have shape [N]")
+        _check(lib.rfsf_ts_features_ragged(ctypes.byref(shp), X.data_ptr(), lengths.data_ptr(), W.data_ptr(),
+                                           hash.data_ptr(), sign.data_ptr(), float(lengthscale), out.data_ptr(),
+                                           workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+        return out[:, :ncols]
     _check(lib.rfsf_ts_features(ctypes.byref(shp), X.data_ptr(), W.data_ptr(), hash.data_ptr(),
                                 sign.data_ptr(), float(lengthscale), out.data_ptr(),
                                 workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))

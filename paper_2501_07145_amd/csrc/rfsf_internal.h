@@ -25,11 +25,13 @@ hipError_t launch_rff_increments(const float *X, const float *W, const float *si
 // (D is the transform length, a power of two; Dout <= D the number of buckets per level: equal to D,
 // or smaller when the buckets are no power of two and the convolutions are linear, folded at the end)
 // columns 0 .. M*D of `n_seq` rows of out (already offset to the chunk).
+// `lengths` (may be null: all L) holds each sequence's own number of points, X being padded to L.
 // `state` is scratch for the generic kernel: n_seq * M * (D/2+1) complex floats.
 // `table` (sketch_fft_scan_table_bytes, filled by launch_pack_tables once per call) feeds the tuned kernel.
 hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
-                                  const uint32_t *table, int64_t n_seq, int64_t L, int M, int F, int D, int Dout,
-                                  int order, float *out, int64_t ld_out, float *state, hipStream_t stream);
+                                  const uint32_t *table, int64_t n_seq, int64_t L, const int64_t *lengths, int M, int F,
+                                  int D, int Dout, int order, float *out, int64_t ld_out, float *state,
+                                  hipStream_t stream);
 hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int F, int D, int Dout,
                               uint32_t *table, hipStream_t stream);
 bool sketch_fft_scan_is_tuned(int M, int F, int D);

@@ -169,9 +169,9 @@ namespace {
 // Body of rfsf_ts_features. `may_create` = false keeps the call free of anything that creates runtime
 // objects: the tables are then built on the caller's stream (no library-owned stream or events) and no
 // profiling events are recorded.
-int features_impl(const rfsf_ts_shape *shape, const float *X, const float *W, const int32_t *hash,
-                  const float *sign, float lengthscale, float *out, void *workspace, size_t workspace_bytes,
-                  void *hip_stream, bool may_create)
+int features_impl(const rfsf_ts_shape *shape, const float *X, const int64_t *lengths, const float *W,
+                  const int32_t *hash, const float *sign, float lengthscale, float *out, void *workspace,
+                  size_t workspace_bytes, void *hip_stream, bool may_create)
 {
     int rc = check_shape(shape);
     if (rc != RFSF_OK) return rc;
@@ -187,10 +187,11 @@ int features_impl(const rfsf_ts_shape *shape, const float *X, const float *W, co
     }
     if ((int64_t)shape->M * ((shape->F + 127) / 128) > 65535) return RFSF_E_UNSUPPORTED;   // grid limits
     if (shape->rff_bf16 != 0 && shape->d > 128) return RFSF_E_UNSUPPORTED;
-    if (shape->order > 2) return RFSF_E_UNSUPPORTED;
+    if (shape->order > 3) return RFSF_E_UNSUPPORTED;
     if ((int64_t)shape->M * 2 * shape->F > ((int64_t)1 << 26)) return RFSF_E_UNSUPPORTED;   // 32-bit row offsets
-    if (!rfsf::sketch_fft_scan_fits(shape->M, shape->F, transform_length(shape->M, shape->D), shape->order == 2 ? 2 : 1))
-        return RFSF_E_UNSUPPORTED;        // the longest transform with order 2: more LDS than a CU has
+    if (!rfsf::sketch_fft_scan_fits(shape->M, shape->F, transform_length(shape->M, shape->D), shape->order < 2 ? 1 : shape->order))
+        return RFSF_E_UNSUPPORTED;        // the longest transform with order 2 (more LDS than a CU has); order 3
+                                          // outside the tuned kernel's shapes
     if (!workspace) return RFSF_E_NULLPTR;
     int64_t chunk = chunk_for(shape, workspace_bytes);
     if (chunk < 1) return RFSF_E_WORKSPACE_TOO_SMALL;
@@ -249,8 +250,9 @@ int features_impl(const rfsf_ts_shape *shape, const float *X, const float *W, co
         }
         {
             rfsf::ProfileScope scope(rfsf::kSketchFftScan, stream, may_create);
-            if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, table, cnt, shape->L, shape->M, shape->F, P, shape->D,
-                                             shape->order == 2 ? 2 : 1, out + n0 * shape->ld_out, shape->ld_out, state, stream) != hipSuccess)
+            if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, table, cnt, shape->L, lengths ? lengths + n0 : nullptr,
+                                             shape->M, shape->F, P, shape->D, shape->order < 2 ? 1 : shape->order,
+                                             out + n0 * shape->ld_out, shape->ld_out, state, stream) != hipSuccess)
                 return RFSF_E_HIP;
         }
     }
@@ -285,7 +287,16 @@ extern "C" int rfsf_ts_features(const rfsf_ts_shape *shape, const float *X, cons
                                 const int32_t *hash, const float *sign, float lengthscale, float *out,
                                 void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    return features_impl(shape, X, W, hash, sign, lengthscale, out, workspace, workspace_bytes, hip_stream, true);
+    return features_impl(shape, X, nullptr, W, hash, sign, lengthscale, out, workspace, workspace_bytes, hip_stream,
+                         true);
+}
+
+extern "C" int rfsf_ts_features_ragged(const rfsf_ts_shape *shape, const float *X, const int64_t *lengths,
+                                       const float *W, const int32_t *hash, const float *sign, float lengthscale,
+                                       float *out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return features_impl(shape, X, lengths, W, hash, sign, lengthscale, out, workspace, workspace_bytes, hip_stream,
+                         true);
 }
 
 extern "C" int rfsf_ts_features_static(const rfsf_ts_shape *shape, const float *X, const float *W,
@@ -302,7 +313,8 @@ extern "C" int rfsf_ts_features_static(const rfsf_ts_shape *shape, const float *
     }
     void *ptr = static_scratch_address();
     if (!ptr) return RFSF_E_HIP;
-    return features_impl(shape, X, W, hash, sign, lengthscale, out, ptr, kStaticScratchBytes, hip_stream, false);
+    return features_impl(shape, X, nullptr, W, hash, sign, lengthscale, out, ptr, kStaticScratchBytes, hip_stream,
+                         false);
 }
 
 extern "C" int rfsf_ts_validate_tables(const int32_t *hash, const float *sign, int32_t M, int32_t F,

@@ -49,8 +49,8 @@ __device__ float2 *fft_workgroup(float2 *in, float2 *out, const float2 *tw, int 
 // accumulators in global scratch. Correct everywhere, tuned nowhere.
 __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
     const float *__restrict__ dphi, const int32_t *__restrict__ hash, const float *__restrict__ sign,
-    int64_t L, int M, int F, int D, int log2D, int Dout, int order, float *__restrict__ out, int64_t ld_out,
-    float2 *__restrict__ state)
+    int64_t L, const int64_t *__restrict__ lengths, int M, int F, int D, int log2D, int Dout, int order,
+    float *__restrict__ out, int64_t ld_out, float2 *__restrict__ state)
 {
     extern __shared__ float2 sm[];
     const int nb = D / 2 + 1;
@@ -58,7 +58,9 @@ __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
     float2 *P0 = tw + D / 2, *P1 = P0 + nb;
     float2 *Q0 = P1 + nb, *Q1 = Q0 + nb, *C0p = Q1 + nb, *C1p = C0p + nb;     // order 2 only (allocated then)
     const int64_t n = blockIdx.x;
-    const int64_t T = L - 1;
+    // this sequence's own number of points when the batch has variable lengths (clamped to [1, L])
+    const int64_t Ln = lengths ? (lengths[n] < 1 ? 1 : (lengths[n] > L ? L : lengths[n])) : L;
+    const int64_t T = Ln - 1;
     const int twoF = 2 * F;
     const int64_t rf = (int64_t)M * twoF;
     float2 *A = state + n * M * nb;
@@ -271,7 +273,7 @@ size_t generic_lds_bytes(int D, int order)
 
 bool sketch_fft_scan_fits(int M, int F, int D, int order)
 {
-    return sketch_fft_scan_is_tuned(M, F, D) || generic_lds_bytes(D, order) <= kLdsPerCu;
+    return sketch_fft_scan_is_tuned(M, F, D) || (order <= 2 && generic_lds_bytes(D, order) <= kLdsPerCu);
 }
 
 size_t sketch_fft_scan_table_bytes(int M, int F, int D)
@@ -303,22 +305,24 @@ hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int
 }
 
 hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
-                                  const uint32_t *table, int64_t n_seq, int64_t L, int M, int F, int D, int Dout,
-                                  int order, float *out, int64_t ld_out, float *state, hipStream_t stream)
+                                  const uint32_t *table, int64_t n_seq, int64_t L, const int64_t *lengths, int M, int F,
+                                  int D, int Dout, int order, float *out, int64_t ld_out, float *state,
+                                  hipStream_t stream)
 {
     if (n_seq == 0) return hipSuccess;
     int log2D = 0;
     while ((1 << log2D) < D) ++log2D;
     if (sketch_fft_scan_is_tuned(M, F, D)) {
         switch (log2D) {
-            case 6: return tuned::dispatch_levels_6(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
-            case 7: return tuned::dispatch_levels_7(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
-            case 8: return tuned::dispatch_levels_8(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
-            case 9: return tuned::dispatch_levels_9(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
-            case 10: return tuned::dispatch_levels_10(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
-            default: return tuned::dispatch_levels_11(M, order, dphi, table, n_seq, L, F, Dout, out, ld_out, stream);
+            case 6: return tuned::dispatch_levels_6(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            case 7: return tuned::dispatch_levels_7(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            case 8: return tuned::dispatch_levels_8(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            case 9: return tuned::dispatch_levels_9(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            case 10: return tuned::dispatch_levels_10(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            default: return tuned::dispatch_levels_11(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
         }
     }
+    if (order > 2) return hipErrorInvalidValue;           // order 3 exists in the tuned kernel only
     const size_t lds = generic_lds_bytes(D, order);
     if (lds > kLdsPerCu) return hipErrorInvalidValue;     // the API layer rejects these shapes up front
     static size_t lds_granted = 0;        // per process; raising the limit is idempotent
@@ -329,7 +333,8 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
         lds_granted = lds;
     }
     hipLaunchKernelGGL(sketch_fft_scan_generic, dim3((unsigned)n_seq), dim3(256), lds, stream,
-                       dphi, hash, sign, L, M, F, D, log2D, Dout, order, out, ld_out, reinterpret_cast<float2 *>(state));
+                       dphi, hash, sign, L, lengths, M, F, D, log2D, Dout, order, out, ld_out,
+                       reinterpret_cast<float2 *>(state));
     return hipGetLastError();
 }
 

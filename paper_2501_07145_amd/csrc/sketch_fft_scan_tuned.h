@@ -24,7 +24,8 @@
 //   then, after one barrier, every thread owns a few frequency bins, separates the two real
 //   transforms of each slot, and advances the accumulators A_1..A_M of its bins by the two
 //   time steps (A_m += A_{m-1}(before the step) * C_m, A_0 = 1; with signature order 2 also
-//   + 1/2 A_{m-2}(before the step) * C_{m-1} * C_m, Sec. 3.5 eq. (ts_rec) with q = 2).
+//   + 1/2 A_{m-2}(before the step) * C_{m-1} * C_m, with order 3 also + 1/6 A_{m-3} C_{m-2} C_{m-1} C_m:
+//   Sec. 3.5 eq. (ts_rec), the terms q = 2, 3).
 //   After the last time step, wavefront m transforms A_m back and writes block m of the row.
 //   (Fetching the next iteration's rows ahead of time was tried in several placements and was never
 //   faster: the pace is set by the instruction streams of the resident workgroups, not by the load
@@ -313,8 +314,8 @@ struct WaveFft {
 template <int LOG2D, int M, int ORDER>
 __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
     __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::WPL == 1 ? 4 : 3, 4))) void sketch_fft_scan_kernel(
-    const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L, int F, int Dout,
-    float *__restrict__ out, int64_t ld_out)
+    const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L,
+    const int64_t *__restrict__ lengths, int F, int Dout, float *__restrict__ out, int64_t ld_out)
 {
     using P = Plan<LOG2D>;
     constexpr int D = P::D, NT = 64 * M * P::WPL, NB = D / 2 + 1, BPT = (NB + NT - 1) / NT;
@@ -329,7 +330,11 @@ __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
     float2 *wave_lds = lds + (size_t)m * P::FPW * PS;
     float2 *my_slot = wave_lds + slot_id * PS;
     char *my_slot_bytes = reinterpret_cast<char *>(my_slot);
-    const int64_t n = blockIdx.x, T = L - 1;
+    const int64_t n = blockIdx.x;
+    // this sequence's own number of points (variable-length batch: X is padded to L points, the steps beyond a
+    // sequence's length do not exist); out-of-range entries are clamped, they are never used as addresses
+    const int64_t Ln = lengths ? (lengths[n] < 1 ? 1 : (lengths[n] > L ? L : lengths[n])) : L;
+    const int64_t T = Ln - 1;
     const int64_t pairs = (T + 1) / 2;
     // pair p of this level: 2F float2 at seq + p * pf (pair layout of the producing kernel, Lp / 2 pair slots
     // per sequence with Lp = L rounded up to even)
@@ -438,9 +443,11 @@ __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
                 if (f < NB) {
                     const int fi = pad(f), fc = pad((D - f) & (D - 1));
                     float2 p0 = make_float2(1.f, 0.f), p1 = make_float2(1.f, 0.f);
-                    // order 2 (a time step may be used twice in a row, weight 1/2): also the values of
-                    // level l-2 before each step and the transforms of level l-1 at both steps
+                    // order >= 2 (a time step may be used up to `order` times in a row, q equal indices weighted
+                    // 1/q!): also the values of levels l-2 (and l-3) before each step and the transforms of
+                    // levels l-1 (and l-2) at both steps
                     float2 q0 = make_float2(0.f, 0.f), q1 = q0, c0p = q0, c1p = q0;
+                    float2 r0 = q0, r1 = q0, c0pp = q0, c1pp = q0;
 #pragma unroll
                     for (int l = 0; l < M; ++l) {
                         const float2 *Z = lds + ((size_t)l * P::FPW + s) * PS;
@@ -452,18 +459,37 @@ __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
                         if (!second_step) C1 = make_float2(0.f, 0.f);
                         const float2 a_old = A[b][l];
                         float2 a_mid = cfmaf(p0, C0, a_old);
-                        if constexpr (ORDER == 2) {
+                        float2 h0 = make_float2(0.f, 0.f), h1 = h0;
+                        if constexpr (ORDER >= 2) {
                             if (l > 0) {
-                                const float2 h = cmulf(c0p, C0);
-                                a_mid = cfmaf(make_float2(0.5f * q0.x, 0.5f * q0.y), h, a_mid);
+                                h0 = cmulf(c0p, C0);
+                                a_mid = cfmaf(make_float2(0.5f * q0.x, 0.5f * q0.y), h0, a_mid);
+                            }
+                        }
+                        if constexpr (ORDER >= 3) {
+                            if (l > 1) {
+                                const float2 g = cmulf(c0pp, h0);
+                                a_mid = cfmaf(make_float2(r0.x * (1.0f / 6.0f), r0.y * (1.0f / 6.0f)), g, a_mid);
                             }
                         }
                         float2 a_new = cfmaf(p1, C1, a_mid);
-                        if constexpr (ORDER == 2) {
+                        if constexpr (ORDER >= 2) {
                             if (l > 0) {
-                                const float2 h = cmulf(c1p, C1);
-                                a_new = cfmaf(make_float2(0.5f * q1.x, 0.5f * q1.y), h, a_new);
+                                h1 = cmulf(c1p, C1);
+                                a_new = cfmaf(make_float2(0.5f * q1.x, 0.5f * q1.y), h1, a_new);
                             }
+                        }
+                        if constexpr (ORDER >= 3) {
+                            if (l > 1) {
+                                const float2 g = cmulf(c1pp, h1);
+                                a_new = cfmaf(make_float2(r1.x * (1.0f / 6.0f), r1.y * (1.0f / 6.0f)), g, a_new);
+                            }
+                            r0 = q0;
+                            r1 = q1;
+                            c0pp = c0p;
+                            c1pp = c1p;
+                        }
+                        if constexpr (ORDER >= 2) {
                             q0 = p0;
                             q1 = p1;
                             c0p = C0;

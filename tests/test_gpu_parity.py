@@ -269,5 +269,68 @@ def test_signature_order_two(oracle, N, L, d, M, F, D):
     if L > 2:
         assert block_errors(got, one, M, D)[1:].max() > 1e-3       # it is not the order-1 map
     with pytest.raises(binding.RfsfTsError) as e:
-        _gpu_features(inp, D, order=3)
+        _gpu_features(inp, D, order=4)
     assert e.value.code == -9
+
+
+@pytest.mark.parametrize("N,L,d,M,F,D", [
+    (4, 12, 3, 3, 32, 64),      # several pairs per wavefront
+    (3, 9, 4, 5, 64, 1024),     # one pair per wavefront
+    (2, 11, 3, 8, 16, 256),     # eight levels
+    (2, 7, 2, 3, 20, 100),      # bucket count that is no power of two (transform length 512)
+    (2, 2, 3, 4, 16, 256),      # one increment: level 3 = (1/6) c_1 * c_2 * c_3
+    (5, 30, 5, 4, 128, 512),    # odd number of increments, two pairs per wavefront
+    (2, 6, 3, 3, 40, 2048),     # a transform spanning two wavefronts
+])
+def test_signature_order_three(oracle, N, L, d, M, F, D):
+    """A time step may be used up to three times in a row, q equal indices weighted 1/q! (Sec. 2.1; Sec. 3.5
+    eq. (ts_rec), q = 1, 2, 3)."""
+    inp = _random_case(500 + D + L, N, L, d, M, F, D)
+    got = _gpu_features(inp, D, order=3).cpu().numpy()
+    want = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D, order=3)
+    err = block_errors(got, want, M, D)
+    print(f"order 3, D={D} M={M}: block errors", err)
+    assert np.all(err <= FP32_BLOCK_TOL)
+    two = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D, order=2)
+    if M >= 3:
+        assert block_errors(got, two, M, D)[2:].max() > 1e-3        # it is not the order-2 map
+    if D == 64:     # outside the tuned kernel's shapes order 3 is refused
+        small = _random_case(1, 2, 6, 2, 2, 4, 16)
+        with pytest.raises(binding.RfsfTsError) as e:
+            _gpu_features(small, 16, order=3)
+        assert e.value.code == -9
+
+
+@pytest.mark.parametrize("N,L,d,M,F,D,order", [
+    (9, 33, 3, 3, 32, 64, 1),       # several pairs per wavefront
+    (7, 20, 4, 5, 64, 1024, 1),     # one pair per wavefront
+    (6, 17, 3, 4, 100, 2048, 1),    # a transform spanning two wavefronts
+    (6, 14, 2, 3, 6, 16, 1),        # generic kernel
+    (6, 19, 3, 4, 32, 256, 2),      # order 2
+    (5, 12, 2, 3, 20, 100, 3),      # order 3, bucket count that is no power of two
+])
+def test_variable_length_batches(oracle, N, L, d, M, F, D, order):
+    """Sequences of different lengths padded to L (appendix, ksig.preprocessing): row n equals the feature map of
+    the first lengths[n] points alone, whatever the padding holds."""
+    inp = _random_case(600 + D + L, N, L, d, M, F, D)
+    rng = np.random.default_rng(L)
+    lengths = rng.integers(1, L + 1, size=N)
+    lengths[:4] = [L, 1, 2, L - 1]                                     # full, no increment, one, odd/even mix
+    X = inp["X"].copy()
+    for n, ell in enumerate(lengths):
+        X[n, ell:] = 1e4 * (n + 1)                                     # padding content must not matter
+    t = _dev(inp)
+    got = rfsf.rfsf_ts_features(torch.from_numpy(X).cuda(), t["W"], t["hash"], t["sign"], inp["lengthscale"], D,
+                                order=order, lengths=torch.from_numpy(lengths).cuda())
+    torch.cuda.synchronize()
+    want = oracle.features_ragged(inp["X"], lengths, inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D,
+                                  order=order)
+    err = block_errors(got.cpu().numpy(), want, M, D)
+    print(f"variable lengths {lengths.tolist()}, D={D} M={M} order {order}: block errors", err)
+    assert np.all(err <= FP32_BLOCK_TOL)
+    # out-of-range entries are clamped into [1, L]
+    bad = torch.from_numpy(np.array([0, -5, L + 7] + [L] * (N - 3))).cuda()
+    got2 = rfsf.rfsf_ts_features(t["X"], t["W"], t["hash"], t["sign"], inp["lengthscale"], D, order=order,
+                                 lengths=bad).cpu().numpy()
+    full = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D, order=order)
+    assert np.all(got2[:2, 1:] == 0.0) and np.all(block_errors(got2[2:], full[2:], M, D) <= FP32_BLOCK_TOL)

@@ -134,6 +134,28 @@ def test_repeated_time_point_changes_nothing(oracle):
                                oracle.features(X, W, hash_, sign, ls, 8), rtol=0, atol=1e-14)
 
 
+def test_variable_lengths_equal_padding_with_the_last_point(oracle):
+    """A sequence of n points padded to L by repeating its last point has the same features (the padding adds
+    zero increments), also for higher signature orders; and the padded region's content is irrelevant."""
+    X, W, hash_, sign, ls = _case(16, N=5, L=9, d=2, M=3, F=4, D=8)
+    lengths = np.array([9, 1, 4, 2, 7])
+    Xp = X.copy()
+    for n, ell in enumerate(lengths):
+        Xp[n, ell:] = X[n, ell - 1]
+    for order in (1, 2, 3):
+        want = oracle.features(Xp, W, hash_, sign, ls, 8, order=order)
+        got = oracle.features_ragged(X, lengths, W, hash_, sign, ls, 8, order=order)
+        np.testing.assert_allclose(got, want, rtol=0, atol=1e-14)
+    junk = X.copy()
+    for n, ell in enumerate(lengths):
+        junk[n, ell:] = 1e3
+    np.testing.assert_array_equal(oracle.features_ragged(junk, lengths, W, hash_, sign, ls, 8),
+                                  oracle.features_ragged(X, lengths, W, hash_, sign, ls, 8))
+    assert np.all(oracle.features_ragged(X, lengths, W, hash_, sign, ls, 8)[1, 1:] == 0.0)      # one point: (1, 0, ..)
+    with pytest.raises(ValueError):
+        oracle.features_ragged(X, np.array([9, 0, 4, 2, 7]), W, hash_, sign, ls, 8)
+
+
 def test_short_sequences(oracle):
     """Empty sums: L = 1 gives (1, 0, ..); level m vanishes when m > T."""
     X, W, hash_, sign, ls = _case(7, N=2, L=3, d=2, M=4, F=4, D=8)
