@@ -361,7 +361,7 @@ def bench_ts(args, name: str, steps: int, warmup: int, cpu_baseline: bool) -> di
     if cpu_baseline:
         import oracle
         from tests.parity import block_errors, gram_error
-        default_rows = {"tiny": 16, "small": 1000, "medium": 32, "long": 16, "large": 32, "paper": 100}[w.name]
+        default_rows = {"tiny": 16, "small": 1000, "medium": 512, "long": 128, "large": 256, "paper": 100}[w.name]
         rows = min(w.N, default_rows if args.cpu_rows < 0 else args.cpu_rows)
         sel = np.linspace(0, w.N - 1, rows).round().astype(np.int64)
         Xs = inp["X"][sel]
