@@ -8,7 +8,7 @@
  *   d  state dimension                M  truncation level
  *   F  random Fourier frequencies per level [paper: D]; the static features have 2F dims
  *   D  count-sketch buckets per level [paper: Q]; a power of two in [2, 4096] is fastest; any other
- *      D is accepted as long as M*(D-1)+1 <= 4096 (the convolutions are then evaluated as linear
+ *      D is accepted as long as M*(D-1)+1 <= 8192 (the convolutions are then evaluated as linear
  *      ones with a longer power-of-two transform and folded modulo D at the end)
  *
  * General rules for every entry point
@@ -44,7 +44,7 @@ enum {
     RFSF_E_NULLPTR = -1,            /* a required pointer is NULL                         */
     RFSF_E_BAD_SHAPE = -2,          /* N < 0, L < 1, d < 1, M < 1, F < 1 or size overflow */
     RFSF_E_D_NOT_POW2 = -3,         /* D neither a power of two in [2, 4096] nor small    */
-                                    /* enough for the linear route, M*(D-1)+1 <= 4096     */
+                                    /* enough for the linear route, M*(D-1)+1 <= 8192     */
     RFSF_E_BAD_STRIDE = -4,         /* a leading dimension is smaller than the row        */
     RFSF_E_BAD_LENGTHSCALE = -5,    /* lengthscale is not a finite number > 0             */
     RFSF_E_WORKSPACE_TOO_SMALL = -6,/* workspace cannot hold one chunk (see below)        */

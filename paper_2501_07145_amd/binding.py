@@ -121,9 +121,9 @@ def _shape_of(X, W, hash_, D, ld_out, rff_bf16, order=1) -> _Shape:
     return _Shape(N, L, d, M, F, int(D), int(ld_out), int(bool(rff_bf16)), int(order))
 
 
-def rfsf_ts_workspace_bytes(N: int, L: int, d: int, M: int, F: int, D: int, rff_bf16: bool = False):
+def rfsf_ts_workspace_bytes(N: int, L: int, d: int, M: int, F: int, D: int, rff_bf16: bool = False, order: int = 1):
     """(recommended_bytes, minimum_bytes) of scratch for rfsf_ts_features."""
-    shp = _Shape(N, L, d, M, F, D, 1 + M * D, int(bool(rff_bf16)))
+    shp = _Shape(N, L, d, M, F, D, 1 + M * D, int(bool(rff_bf16)), int(order))
     rec, mn = ctypes.c_size_t(0), ctypes.c_size_t(0)
     _check(load_library().rfsf_ts_workspace_bytes(ctypes.byref(shp), ctypes.byref(rec), ctypes.byref(mn)))
     return int(rec.value), int(mn.value)
@@ -161,7 +161,7 @@ def rfsf_ts_features(X: torch.Tensor, W: torch.Tensor, hash: torch.Tensor, sign:
     ld_out = out.stride(0) if N > 1 else max(out.stride(0), out.shape[1])
     shp = _shape_of(X, W, hash, D, ld_out, rff_bf16, order)
     if workspace is None:
-        rec, _ = rfsf_ts_workspace_bytes(shp.N, shp.L, shp.d, shp.M, shp.F, shp.D, rff_bf16)
+        rec, _ = rfsf_ts_workspace_bytes(shp.N, shp.L, shp.d, shp.M, shp.F, shp.D, rff_bf16, order)
         workspace = _empty_on(stream, rec, dtype=torch.uint8, device=X.device)
     workspace = _dev(workspace, torch.uint8, "workspace")
     if lengths is not None:

@@ -26,7 +26,8 @@ hipError_t launch_rff_increments(const float *X, const float *W, const float *si
 // or smaller when the buckets are no power of two and the convolutions are linear, folded at the end)
 // columns 0 .. M*D of `n_seq` rows of out (already offset to the chunk).
 // `lengths` (may be null: all L) holds each sequence's own number of points, X being padded to L.
-// `state` is scratch for the generic kernel: n_seq * M * (D/2+1) complex floats.
+// `state` is scratch for the generic kernel: sketch_fft_scan_state_bytes (accumulators, and the work buffers
+// when they do not fit in LDS).
 // `table` (sketch_fft_scan_table_bytes, filled by launch_pack_tables once per call) feeds the tuned kernel.
 hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
                                   const uint32_t *table, int64_t n_seq, int64_t L, const int64_t *lengths, int M, int F,
@@ -38,7 +39,7 @@ bool sketch_fft_scan_is_tuned(int M, int F, int D);
 bool sketch_fft_scan_fits(int M, int F, int D, int order);  // false: neither kernel can run it (LDS need above a CU's)
 size_t sketch_fft_scan_table_bytes(int M, int F, int D);   // 0 when the generic kernel runs
 size_t sketch_fft_scan_lds_bytes(int M, int F, int D);
-size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D);
+size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D, int order);
 
 // Level-0 column and zero blocks for sequences without increments (L == 1).
 hipError_t launch_fill_trivial(float *out, int64_t n_seq, int64_t ld_out, int64_t ncols, hipStream_t stream);

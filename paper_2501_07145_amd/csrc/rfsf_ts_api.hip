@@ -45,7 +45,8 @@ bool is_pow2_in_range(int32_t D) { return D >= 2 && D <= 4096 && (D & (D - 1)) =
 // Length of the FFTs. A power-of-two bucket count is transformed as it is (circular convolution
 // modulo D). Any other D >= 1 takes the next power of two that holds the linear convolution of M
 // sketches of length D without wrap-around, M*(D-1)+1 numbers; the kernels fold the result modulo D
-// at the end. 0 if that exceeds the largest transform.
+// at the end. 0 if that exceeds the largest transform (8192, which covers the paper's own largest
+// projection size, 1000, at its truncation level 5).
 int transform_length(int32_t M, int32_t D)
 {
     if (is_pow2_in_range(D)) return D;
@@ -53,7 +54,7 @@ int transform_length(int32_t M, int32_t D)
     const int64_t need = (int64_t)M * (D - 1) + 1;
     int64_t P = 2;
     while (P < need) P *= 2;
-    return P <= 4096 ? (int)P : 0;
+    return P <= 8192 ? (int)P : 0;
 }
 
 int check_shape(const rfsf_ts_shape *s)
@@ -74,7 +75,7 @@ void per_sequence_bytes(const rfsf_ts_shape *s, size_t *incr, size_t *state)
 {
     // rows of increments per sequence: L in the row layout, L rounded up to even in the pair layout
     *incr = (size_t)((s->L + 1) & ~(int64_t)1) * (size_t)s->M * 2u * (size_t)s->F * sizeof(float);
-    *state = rfsf::sketch_fft_scan_state_bytes(1, s->M, transform_length(s->M, s->D));
+    *state = rfsf::sketch_fft_scan_state_bytes(1, s->M, transform_length(s->M, s->D), s->order == 2 ? 2 : 1);
 }
 
 // Fixed part: packed hash/sign table plus room for aligning the three sections.
@@ -131,7 +132,7 @@ extern "C" const char *rfsf_ts_strerror(int code)
         case RFSF_OK: return "success";
         case RFSF_E_NULLPTR: return "a required pointer is NULL";
         case RFSF_E_BAD_SHAPE: return "bad shape: need N >= 0, L >= 1, d >= 1, M >= 1, F >= 1 within limits";
-        case RFSF_E_D_NOT_POW2: return "D must be a power of two in [2, 4096], or satisfy M*(D-1)+1 <= 4096";
+        case RFSF_E_D_NOT_POW2: return "D must be a power of two in [2, 4096], or satisfy M*(D-1)+1 <= 8192";
         case RFSF_E_BAD_STRIDE: return "leading dimension smaller than the row length";
         case RFSF_E_BAD_LENGTHSCALE: return "lengthscale must be finite and > 0";
         case RFSF_E_WORKSPACE_TOO_SMALL: return "workspace smaller than rfsf_ts_workspace_bytes' minimum";
@@ -190,8 +191,7 @@ int features_impl(const rfsf_ts_shape *shape, const float *X, const int64_t *len
     if (shape->order > 3) return RFSF_E_UNSUPPORTED;
     if ((int64_t)shape->M * 2 * shape->F > ((int64_t)1 << 26)) return RFSF_E_UNSUPPORTED;   // 32-bit row offsets
     if (!rfsf::sketch_fft_scan_fits(shape->M, shape->F, transform_length(shape->M, shape->D), shape->order < 2 ? 1 : shape->order))
-        return RFSF_E_UNSUPPORTED;        // the longest transform with order 2 (more LDS than a CU has); order 3
-                                          // outside the tuned kernel's shapes
+        return RFSF_E_UNSUPPORTED;        // order 3 outside the tuned kernel's shapes
     if (!workspace) return RFSF_E_NULLPTR;
     int64_t chunk = chunk_for(shape, workspace_bytes);
     if (chunk < 1) return RFSF_E_WORKSPACE_TOO_SMALL;

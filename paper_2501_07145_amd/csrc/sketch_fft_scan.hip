@@ -45,16 +45,27 @@ __device__ float2 *fft_workgroup(float2 *in, float2 *out, const float2 *tw, int 
     return in;
 }
 
-// Generic kernel: any power-of-two D in [2, 4096], any M and F. One workgroup per sequence,
+// float2 elements of the generic kernel's work buffers: two transform buffers, twiddles, the previous level's
+// values before each of the two steps (order 2: also level m-2's and the previous level's transforms).
+__host__ __device__ constexpr int64_t generic_buffer_elems(int D, int order)
+{
+    return 2 * (int64_t)D + D / 2 + (order == 2 ? 6 : 2) * (int64_t)(D / 2 + 1);
+}
+
+// Generic kernel: any power-of-two transform length D in [2, 8192], any M and F. One workgroup per sequence,
 // accumulators in global scratch. Correct everywhere, tuned nowhere.
 __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
     const float *__restrict__ dphi, const int32_t *__restrict__ hash, const float *__restrict__ sign,
     int64_t L, const int64_t *__restrict__ lengths, int M, int F, int D, int log2D, int Dout, int order,
-    float *__restrict__ out, int64_t ld_out, float2 *__restrict__ state)
+    float *__restrict__ out, int64_t ld_out, float2 *__restrict__ state, float2 *__restrict__ scratch)
 {
     extern __shared__ float2 sm[];
     const int nb = D / 2 + 1;
-    float2 *buf0 = sm, *buf1 = sm + D, *tw = sm + 2 * D;
+    // Work buffers: in LDS when they fit a CU's 160 KB, otherwise (`scratch` not null: transforms of 8192, or
+    // of 4096 with order 2) in this sequence's part of the workspace, where they stay L2-resident. The
+    // workgroup barriers between the passes make the global writes visible to the whole workgroup.
+    float2 *base = scratch ? scratch + (int64_t)blockIdx.x * generic_buffer_elems(D, order) : sm;
+    float2 *buf0 = base, *buf1 = base + D, *tw = base + 2 * D;
     float2 *P0 = tw + D / 2, *P1 = P0 + nb;
     float2 *Q0 = P1 + nb, *Q1 = Q0 + nb, *C0p = Q1 + nb, *C1p = C0p + nb;     // order 2 only (allocated then)
     const int64_t n = blockIdx.x;
@@ -231,9 +242,17 @@ __global__ void validate_tables_kernel(const int32_t *hash, const float *sign, i
 
 }  // namespace
 
-size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D)
+namespace {
+constexpr size_t kLdsPerCu = 160 * 1024;
+size_t generic_lds_bytes(int D, int order) { return sizeof(float2) * (size_t)generic_buffer_elems(D, order); }
+bool generic_in_global(int D, int order) { return generic_lds_bytes(D, order) > kLdsPerCu; }
+}  // namespace
+
+size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D, int order)
 {
-    return (size_t)n_seq * (size_t)M * (size_t)(D / 2 + 1) * sizeof(float2);
+    size_t per = (size_t)M * (size_t)(D / 2 + 1) * sizeof(float2);
+    if (generic_in_global(D, order)) per += generic_lds_bytes(D, order);     // work buffers behind the accumulators
+    return (size_t)n_seq * per;
 }
 
 namespace {
@@ -247,7 +266,6 @@ bool tuned_geometry(int D, TunedGeometry *g)
         default: return false;
     }
 }
-constexpr size_t kLdsPerCu = 160 * 1024;
 }  // namespace
 
 size_t sketch_fft_scan_lds_bytes(int M, int F, int D)
@@ -264,16 +282,9 @@ bool sketch_fft_scan_is_tuned(int M, int F, int D)
     return sketch_fft_scan_lds_bytes(M, F, D) <= kLdsPerCu;
 }
 
-namespace {
-size_t generic_lds_bytes(int D, int order)
-{
-    return sizeof(float2) * (size_t)(2 * D + D / 2 + (order == 2 ? 6 : 2) * (D / 2 + 1));
-}
-}  // namespace
-
 bool sketch_fft_scan_fits(int M, int F, int D, int order)
 {
-    return sketch_fft_scan_is_tuned(M, F, D) || (order <= 2 && generic_lds_bytes(D, order) <= kLdsPerCu);
+    return sketch_fft_scan_is_tuned(M, F, D) || order <= 2;
 }
 
 size_t sketch_fft_scan_table_bytes(int M, int F, int D)
@@ -323,8 +334,8 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
         }
     }
     if (order > 2) return hipErrorInvalidValue;           // order 3 exists in the tuned kernel only
-    const size_t lds = generic_lds_bytes(D, order);
-    if (lds > kLdsPerCu) return hipErrorInvalidValue;     // the API layer rejects these shapes up front
+    const bool in_global = generic_in_global(D, order);
+    const size_t lds = in_global ? 0 : generic_lds_bytes(D, order);
     static size_t lds_granted = 0;        // per process; raising the limit is idempotent
     if (lds > 64 * 1024 && lds > lds_granted) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(sketch_fft_scan_generic),
@@ -332,9 +343,10 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
         if (e != hipSuccess) return e;
         lds_granted = lds;
     }
+    float2 *acc = reinterpret_cast<float2 *>(state);
+    float2 *scratch = in_global ? acc + n_seq * M * (D / 2 + 1) : nullptr;
     hipLaunchKernelGGL(sketch_fft_scan_generic, dim3((unsigned)n_seq), dim3(256), lds, stream,
-                       dphi, hash, sign, L, lengths, M, F, D, log2D, Dout, order, out, ld_out,
-                       reinterpret_cast<float2 *>(state));
+                       dphi, hash, sign, L, lengths, M, F, D, log2D, Dout, order, out, ld_out, acc, scratch);
     return hipGetLastError();
 }
 

@@ -52,7 +52,7 @@ def _shape(**kw):
 
 @pytest.mark.parametrize("kw,code", [
     (dict(N=-1), -2), (dict(L=0), -2), (dict(d=0), -2), (dict(M=0), -2), (dict(F=0), -2),
-    (dict(D=3000, ld_out=6001), -3), (dict(D=8192, ld_out=16385), -3), (dict(D=0), -3), (dict(D=-4), -3),
+    (dict(D=4099, ld_out=8199), -3), (dict(D=8192, ld_out=16385), -3), (dict(D=3000, M=4, ld_out=12001), -3), (dict(D=0), -3), (dict(D=-4), -3),
     (dict(ld_out=16), -4),
 ])
 def test_shape_validation(kw, code):
@@ -88,17 +88,20 @@ def test_argument_validation_without_device_access():
 def test_bucket_counts_that_are_no_power_of_two_are_accepted_when_small():
     lib = binding.load_library()
     rec, mn = ctypes.c_size_t(0), ctypes.c_size_t(0)
-    for D, M, ok in ((6, 2, True), (100, 5, True), (200, 5, True), (1000, 5, False), (1, 3, True), (2049, 2, False)):
+    # (1000, 5) is the paper's own largest projection size at its truncation level: a transform of 8192
+    for D, M, ok in ((6, 2, True), (100, 5, True), (200, 5, True), (1000, 5, True), (1, 3, True), (2049, 2, True),
+                     (1000, 9, False), (4097, 1, False)):
         shp = _shape(D=D, M=M, ld_out=1 + M * D)
         assert (lib.rfsf_ts_workspace_bytes(ctypes.byref(shp), ctypes.byref(rec), ctypes.byref(mn)) == 0) == ok
 
 
-def test_longest_transform_with_order_two_is_refused_before_anything_is_enqueued():
-    # D = 4096 runs the generic kernel, whose LDS need with order 2 exceeds a compute unit's 160 KB
+def test_order_three_outside_the_tuned_shapes_is_refused_before_anything_is_enqueued():
+    # D = 4096 and D = 16 run the generic kernel, which has orders 1 and 2 only
     lib = binding.load_library()
-    shp = _shape(D=4096, ld_out=1 + 2 * 4096, order=2)
-    assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, 1.0, 256, 256, 1 << 30, None) == -9
-    shp = _shape(D=4096, ld_out=1 + 2 * 4096, order=3)
+    for D in (4096, 16):
+        shp = _shape(D=D, ld_out=1 + 2 * D, order=3)
+        assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, 1.0, 256, 256, 1 << 30, None) == -9
+    shp = _shape(D=64, ld_out=1 + 2 * 64, order=4)
     assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, 1.0, 256, 256, 1 << 30, None) == -9
 
 

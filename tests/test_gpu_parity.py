@@ -239,6 +239,9 @@ def test_symmetric_gram_path(oracle, N, C):
     (2, 30, 3, 2, 50, 1000),    # 2048
     (2, 9, 3, 5, 40, 300),      # 2048 through five levels
     (2, 7, 2, 3, 5, 1),         # a single bucket
+    (2, 8, 3, 5, 50, 1000),     # the paper's largest projection size at its truncation level: 8192, buffers in global memory
+    (2, 9, 2, 2, 30, 2049),     # 8192 with two levels
+    (2, 6, 3, 3, 20, 1366),     # 4096 (4096 >= 3*1365+1)
 ])
 def test_bucket_counts_that_are_no_power_of_two(oracle, N, L, d, M, F, D):
     """Circular convolution modulo D through a longer power-of-two transform: the M-fold convolution of
@@ -256,6 +259,8 @@ def test_bucket_counts_that_are_no_power_of_two(oracle, N, L, d, M, F, D):
     (2, 7, 2, 3, 20, 100),      # bucket count that is no power of two
     (2, 2, 3, 4, 16, 256),      # one increment: level 2 = (1/2) c_1 * c_2, levels 3, 4 vanish
     (6, 31, 5, 4, 128, 256),    # odd number of increments
+    (2, 9, 3, 3, 16, 4096),     # longest power-of-two bucket count: the generic kernel's buffers move to global memory
+    (2, 7, 3, 3, 20, 1500),     # 8192 with order 2
 ])
 def test_signature_order_two(oracle, N, L, d, M, F, D):
     """A time step may be used twice in a row, with weight 1/2 (Sec. 2.1; Sec. 3.5 eq. (ts_rec), q = 2)."""
