@@ -233,31 +233,36 @@ __device__ __forceinline__ TileCoord tile_of_rank(int64_t rank, int64_t nti, int
 constexpr int kBigTile = 128;
 constexpr int kBigOperand = kBigTile * kKT;                 // floats of one operand in one buffer
 
-// 64 matrix instructions on the slab staged in `rd`: row (wi or wj)*64 + 32 t + col of each operand, chunk
-// 4 half + c in slot (4 half + c) ^ s(row).
-__device__ __forceinline__ void big_multiply(const float *__restrict__ rd, int frag_a, int frag_b, int half, int fsw,
-                                             floatx16 (&acc)[2][2])
+// Fragments of one lane for k-groups c = C0 .. C0+1 of a staged slab: row (wi or wj)*64 + 32 t + col of each
+// operand, chunk 4 half + c in slot (4 half + c) ^ s(row).
+struct BigFrag { float4 a[2][2], b[2][2]; };           // [c - C0][t]
+template <int C0>
+__device__ __forceinline__ void big_read(const float *__restrict__ rd, int frag_a, int frag_b, int half, int fsw, BigFrag &f)
 {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const int slot = 4 * ((4 * half + c) ^ fsw);
-        float4 fa[2], fb[2];
+    for (int c = 0; c < 2; ++c) {
+        const int slot = 4 * ((4 * half + C0 + c) ^ fsw);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            fa[t] = *reinterpret_cast<const float4 *>(&rd[frag_a + t * 32 * kKT + slot]);
-            fb[t] = *reinterpret_cast<const float4 *>(&rd[frag_b + t * 32 * kKT + slot]);
+            f.a[c][t] = *reinterpret_cast<const float4 *>(&rd[frag_a + t * 32 * kKT + slot]);
+            f.b[c][t] = *reinterpret_cast<const float4 *>(&rd[frag_b + t * 32 * kKT + slot]);
         }
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    const float av = e == 0 ? fa[a].x : e == 1 ? fa[a].y : e == 2 ? fa[a].z : fa[a].w;
-                    const float bv = e == 0 ? fb[b].x : e == 1 ? fb[b].y : e == 2 ? fb[b].z : fb[b].w;
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[a][b], 0, 0, 0);
-                }
     }
+}
+// 16 matrix instructions on k-group c of a fragment pair
+__device__ __forceinline__ void big_mfma16(const BigFrag &f, int c, floatx16 (&acc)[2][2])
+{
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const float4 &fa = f.a[c][a], &fb = f.b[c][b];
+                const float av = e == 0 ? fa.x : e == 1 ? fa.y : e == 2 ? fa.z : fa.w;
+                const float bv = e == 0 ? fb.x : e == 1 ? fb.y : e == 2 ? fb.z : fb.w;
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[a][b], 0, 0, 0);
+            }
 }
 
 // Direct loads of one full slab (columns k0 .. k0+31) into `wr`: wavefront `wave` fills rows 32u + 8 wave .. +7.
@@ -274,25 +279,39 @@ __device__ __forceinline__ void big_load_direct(float *__restrict__ wr, const fl
     }
 }
 
-// One steady-state step: slab in `rd` is multiplied while the next one lands in `wr`. `rd` and `wr` are the two
-// distinct LDS buffers; telling the compiler so (restrict) keeps it from waiting for the loads before the reads.
+// One steady-state step, software-pipelined across the barrier: on entry `f01` holds the fragments of
+// k-groups 0, 1 of the slab in `rd`. The next slab's direct loads go out first and have three quarters of the
+// step to land; the barrier sits before the last 16 matrix instructions, so that the first LDS reads of the next
+// slab (into `f01` again) run under them instead of stalling the matrix pipe after the barrier. `rd` and `wr`
+// are the two distinct LDS buffers; telling the compiler so (restrict) keeps it from waiting for the loads
+// before the reads of `rd`.
 __device__ __forceinline__ void big_step(const float *__restrict__ rd, float *__restrict__ wr,
                                          const float *const (&pa)[4], const float *const (&pb)[4], int64_t k_next,
-                                         int wave, int frag_a, int frag_b, int half, int fsw, floatx16 (&acc)[2][2])
+                                         int wave, int frag_a, int frag_b, int half, int fsw, BigFrag &f01,
+                                         floatx16 (&acc)[2][2])
 {
+    BigFrag f23;
     big_load_direct(wr, pa, pb, k_next, wave);
-    big_multiply(rd, frag_a, frag_b, half, fsw, acc);
-    // order within the step: the loads go out early (they have until the barrier to land), spread between the
-    // first matrix instructions together with the LDS reads of the second half
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);      // LDS reads of the first two k-groups
+    big_read<2>(rd, frag_a, frag_b, half, fsw, f23);
+    big_mfma16(f01, 0, acc);
+    big_mfma16(f01, 1, acc);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);  // 4 matrix instructions
         __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // one direct load of the next slab
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read of the last two k-groups
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read of k-groups 2, 3
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 32, 0);
-    __syncthreads();
+    big_mfma16(f23, 0, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();                                        // next slab complete, this one read by everyone
+    big_read<0>(wr, frag_a, frag_b, half, fsw, f01);
+    big_mfma16(f23, 1, acc);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);  // one LDS read of the next slab's k-groups 0, 1
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 1);  // 2 matrix instructions
+    }
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 template <bool SYM>
@@ -372,20 +391,28 @@ __global__ __launch_bounds__(256, 2) void gram_mfma_big(
         stage_masked(buf0);
     }
     __syncthreads();
+    BigFrag f01, f23;
+    big_read<0>(buf0, frag_a, frag_b, half, fsw, f01);
     int64_t sl = 0;
     // steady state, two slabs per trip so that each step names its buffers statically
     for (; sl + 2 < nfull; sl += 2) {
-        big_step(buf0, buf1, pa, pb, (sl + 1) * kKT, wave, frag_a, frag_b, half, fsw, acc);
-        big_step(buf1, buf0, pa, pb, (sl + 2) * kKT, wave, frag_a, frag_b, half, fsw, acc);
+        big_step(buf0, buf1, pa, pb, (sl + 1) * kKT, wave, frag_a, frag_b, half, fsw, f01, acc);
+        big_step(buf1, buf0, pa, pb, (sl + 2) * kKT, wave, frag_a, frag_b, half, fsw, f01, acc);
     }
-    // the last slabs (at most two full ones and the partial one): loads through registers
+    // the last slabs (at most two full ones and the partial one): loads through registers; `f01` holds the
+    // first half of slab sl
     for (; sl < nslab; ++sl) {
         const bool more = sl + 1 < nslab;
         float *rd = (sl & 1) ? buf1 : buf0, *wr = (sl & 1) ? buf0 : buf1;
         if (more) fetch_masked((sl + 1) * kKT);
-        big_multiply(rd, frag_a, frag_b, half, fsw, acc);
+        big_read<2>(rd, frag_a, frag_b, half, fsw, f23);
+        big_mfma16(f01, 0, acc);
+        big_mfma16(f01, 1, acc);
+        big_mfma16(f23, 0, acc);
+        big_mfma16(f23, 1, acc);
         if (more) stage_masked(wr);
         __syncthreads();
+        if (more) big_read<0>(wr, frag_a, frag_b, half, fsw, f01);
     }
     // result layout of a 32x32 block: lane holds column lane%32 and rows 8q + 4*(lane/32) + i
 #pragma unroll

@@ -189,6 +189,7 @@ __device__ __forceinline__ int64_t padded_row_to_x_row(int64_t G, const PaddedRo
                                                        int64_t Lp)
 {
     G = G < b.G ? b.G : (G >= rows_pad ? rows_pad - 1 : G);
+    if (Lp == L) return G;                                     // even L: the padded row space is the row space of X
     int64_t t = b.t + (G - b.G), n = b.n;                      // G - b.G < 512
     if (Lp >= 512) {
         if (t >= Lp) { t -= Lp; ++n; }
