@@ -278,7 +278,9 @@ size_t sketch_fft_scan_lds_bytes(int M, int F, int D)
 bool sketch_fft_scan_is_tuned(int M, int F, int D)
 {
     TunedGeometry g;
-    if (M > 8 || F > 4095 || !tuned_geometry(D, &g)) return false;
+    // F <= 4032: the staging area (2F rounded up to 128 coordinates) and the zero float2 behind it are
+    // addressed with 16-bit byte offsets
+    if (M > 8 || F > 4032 || !tuned_geometry(D, &g)) return false;
     return sketch_fft_scan_lds_bytes(M, F, D) <= kLdsPerCu;
 }
 

@@ -101,6 +101,10 @@ def test_order_three_outside_the_tuned_shapes_is_refused_before_anything_is_enqu
     for D in (4096, 16):
         shp = _shape(D=D, ld_out=1 + 2 * D, order=3)
         assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, 1.0, 256, 256, 1 << 30, None) == -9
+    # the tuned kernel addresses a slot with 16-bit byte offsets: 4032 random features at most
+    for F, code in ((4032, -6), (4033, -9)):             # -6: accepted as far as the (too small) workspace
+        shp = _shape(D=1024, M=1, F=F, ld_out=1 + 1024, order=3)
+        assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, 1.0, 256, 256, 1024, None) == code
     shp = _shape(D=64, ld_out=1 + 2 * 64, order=4)
     assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, 1.0, 256, 256, 1 << 30, None) == -9
 

@@ -78,6 +78,8 @@ def test_small_64_rows(oracle):
     (3, 50, 5, 7, 33, 128),     # seven levels, D = 128
     (2, 9, 70, 2, 40, 64),      # d above 64: plain vector projection kernel
     (1, 4, 2, 1, 4100, 64),     # 2F above the 16-bit table offsets: generic sketch kernel
+    (1, 5, 2, 1, 4032, 1024),    # the most coordinates the tuned sketch kernel takes (16-bit byte offsets into a slot)
+    (1, 5, 2, 1, 4033, 1024),    # one more: generic sketch kernel
     (2, 12, 3, 2, 600, 256),    # 2F much larger than D: staging area beyond the transform length
 ])
 def test_ragged_shapes(oracle, N, L, d, M, F, D):
