@@ -176,6 +176,20 @@ __device__ __forceinline__ float2 cfmaf(float2 a, float2 b, float2 c)   // a * b
     return make_float2(fmaf(a.x, b.x, fmaf(-a.y, b.y, c.x)), fmaf(a.x, b.y, fmaf(a.y, b.x, c.y)));
 }
 
+// The same for a thread whose float2 are not complex numbers but two independent reals (pk; bins 0 and D/2
+// of a real sequence's transform, which one thread carries in the two halves of its values): the products
+// become componentwise. With pk false these are cmulf and cfmaf, operation for operation.
+__device__ __forceinline__ float2 cmulf_pk(float2 a, float2 b, bool pk)
+{
+    const float s = pk ? 0.f : b.y, r = pk ? b.y : b.x;
+    return make_float2(fmaf(a.x, b.x, -a.y * s), fmaf(a.x, s, a.y * r));
+}
+__device__ __forceinline__ float2 cfmaf_pk(float2 a, float2 b, float2 c, bool pk)
+{
+    const float s = pk ? 0.f : b.y, r = pk ? b.y : b.x;
+    return make_float2(fmaf(a.x, b.x, fmaf(-a.y, s, c.x)), fmaf(a.x, s, fmaf(a.y, r, c.y)));
+}
+
 // Orders the LDS traffic of one wavefront: its LDS instructions execute in order, so only the
 // compiler has to be kept from moving accesses across this point.
 __device__ __forceinline__ void wave_lds_fence()
@@ -311,23 +325,92 @@ struct WaveFft {
     }
 };
 
-template <int LOG2D, int M, int ORDER>
-__global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
+// Number of transforms a workgroup has in flight per iteration (= its wavefronts when a transform lives in one
+// wavefront). Normally one per level. With 5, 6 or 7 levels that would make workgroups of 5-7 wavefronts, and
+// the hardware then keeps far fewer of them resident than registers and LDS allow (measured with an empty
+// kernel of the same footprint, ~116 registers and 51 KB: 1.7 workgroups = 8.6 wavefronts per CU for 5
+// wavefronts per workgroup, 15.6 wavefronts for 4 or 8 per workgroup: the dispatcher reserves registers for
+// ceil(wavefronts / 4) wavefronts on every SIMD). Those level counts therefore run 8 wavefronts that take the
+// (pair, level) transforms of the sequence in order, 8 at a time, whatever level they belong to.
+__host__ __device__ constexpr int transforms_in_flight(int M, int WPL) { return (WPL == 1 && M >= 5 && M <= 7) ? 8 : M; }
+
+template <int LL>
+struct LevelTag {
+    static constexpr int value = LL;
+};
+// Calls f(LevelTag<l>) for a wavefront-uniform runtime level l in [0, M).
+template <int M, int LL = 0, typename Fn>
+__device__ __forceinline__ void with_level(int l, Fn &&f)
+{
+    if constexpr (LL + 1 < M) {
+        if (l == LL) f(LevelTag<LL>{});
+        else with_level<M, LL + 1>(l, f);
+    } else {
+        f(LevelTag<LL>{});
+    }
+}
+
+// What level l of one pair hands to level l+1 of the same pair in the recurrence: the values of A_l before
+// each of the two steps (p), with order >= 2 also those of A_{l-1} (q) and the transforms of level l (cp),
+// with order 3 also those of A_{l-2} (r) and the transforms of level l-1 (cpp).
+template <int ORDER>
+struct LevelCarry {
+    float2 p0, p1;
+    float2 q0, q1, c0p, c1p;        // used with order >= 2
+    float2 r0, r1, c0pp, c1pp;      // used with order 3
+    __device__ __forceinline__ void reset()
+    {
+        p0 = p1 = make_float2(1.f, 0.f);
+        q0 = q1 = c0p = c1p = r0 = r1 = c0pp = c1pp = make_float2(0.f, 0.f);
+    }
+};
+
+// Items J = 0..NTR-1 of an iteration whose first item has level L0: calls f(LevelTag<level of item J>, LevelTag<J>,
+// number of pair groups item J lies behind item 0).
+template <int L0, int M, int NTR, int J = 0, typename Fn>
+__device__ __forceinline__ void item_loop(Fn &&f)
+{
+    if constexpr (J < NTR) {
+        f(LevelTag<(L0 + J) % M>{}, LevelTag<J>{}, (L0 + J) / M);
+        item_loop<L0, M, NTR, J + 1>(f);
+    }
+}
+
+// Calls f(LevelTag<0>), ..., f(LevelTag<M-1>).
+template <int M, int LL = 0, typename Fn>
+__device__ __forceinline__ void level_loop(Fn &&f)
+{
+    if constexpr (LL < M) {
+        f(LevelTag<LL>{});
+        level_loop<M, LL + 1>(f);
+    }
+}
+
+template <int LOG2D, int M, int ORDER, int NTR>
+__global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
     __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::WPL == 1 ? 4 : 3, 4))) void sketch_fft_scan_kernel(
     const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L,
     const int64_t *__restrict__ lengths, int F, int Dout, float *__restrict__ out, int64_t ld_out)
 {
     using P = Plan<LOG2D>;
-    constexpr int D = P::D, NT = 64 * M * P::WPL, NB = D / 2 + 1, BPT = (NB + NT - 1) / NT;
-    extern __shared__ float2 lds[];                    // [M][FPW][PS] slots, then the twiddle table
+    // kStream: the workgroup's NTR transforms of an iteration are the next NTR (pair group, level) items of the
+    // sequence in that order, so a wavefront changes level from iteration to iteration and an iteration
+    // may end in the middle of a pair; otherwise transform w of the workgroup is always level w.
+    constexpr bool kStream = NTR != M;
+    static_assert(!kStream || (P::WPL == 1 && NTR > M), "streaming needs one wavefront per transform and a slot per level");
+    // Bins of phase 3: f = 0 .. D/2 - 1, thread t owning f = t, t + NT, ... The transforms of real sequences are
+    // real at f = 0 and f = D/2; thread 0 carries both in one float2 (bin 0 in .x, bin D/2 in .y), which keeps the
+    // number of bins a power of two.
+    constexpr int D = P::D, NT = 64 * NTR * P::WPL, NB = D / 2, BPT = (NB + NT - 1) / NT;
+    extern __shared__ float2 lds[];                    // [NTR][FPW][PS] slots, then the twiddle table
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int m = wave / P::WPL, sub = wave % P::WPL;        // level, wavefront within the level
+    const int wv = wave / P::WPL, sub = wave % P::WPL;       // transform of the workgroup, wavefront within it
     const int slot_id = P::WPL > 1 ? 0 : lane / P::G;
     const int lg = P::WPL > 1 ? sub * 64 + lane : lane % P::G; // lane within the transform
     const int twoF = 2 * F;
     const int ZS = zero_slot(P::PD, twoF), PS = slot_stride(P::PD, twoF);
-    float2 *twl_table = lds + (size_t)M * P::FPW * PS;          // behind the slots
-    float2 *wave_lds = lds + (size_t)m * P::FPW * PS;
+    float2 *twl_table = lds + (size_t)NTR * P::FPW * PS;        // behind the slots
+    float2 *wave_lds = lds + (size_t)wv * P::FPW * PS;
     float2 *my_slot = wave_lds + slot_id * PS;
     char *my_slot_bytes = reinterpret_cast<char *>(my_slot);
     const int64_t n = blockIdx.x;
@@ -336,14 +419,15 @@ __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
     const int64_t Ln = lengths ? (lengths[n] < 1 ? 1 : (lengths[n] > L ? L : lengths[n])) : L;
     const int64_t T = Ln - 1;
     const int64_t pairs = (T + 1) / 2;
-    // pair p of this level: 2F float2 at seq + p * pf (pair layout of the producing kernel, Lp / 2 pair slots
-    // per sequence with Lp = L rounded up to even)
+    const int64_t groups = (pairs + P::FPW - 1) / P::FPW;    // a transform carries FPW consecutive pairs of one level
+    const int64_t iters = kStream ? (groups * M + NTR - 1) / NTR : groups;
+    // pair p of level l: 2F float2 at seq + l * 2 * twoF + p * pf (pair layout of the producing kernel, Lp / 2
+    // pair slots per sequence with Lp = L rounded up to even)
     const int64_t pf = (int64_t)M * 2 * twoF;
-    const float *seq = dphi + n * ((L + 1) / 2) * pf + (int64_t)m * 2 * twoF;
+    const float *seq = dphi + n * ((L + 1) / 2) * pf;
     const TableLayout tl = table_layout(D, P::GF, twoF);
-    const uint32_t *tab = table + (int64_t)m * tl.words;
-    const int NG = (int)tab[0];
     const int nload = staged(twoF) / 128;                    // direct loads per pair, 128 coordinates each
+    const int NG_fixed = kStream ? 0 : (int)table[(int64_t)wv * tl.words];   // fold rounds of the wavefront's fixed level
 
     WaveFft<P> fft;
     fft.init(lg, twl_table);
@@ -356,16 +440,16 @@ __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
 #pragma unroll
         for (int l = 0; l < M; ++l) A[b][l] = make_float2(0.f, 0.f);
 
-    // Staging: pair pair0 + s goes to slot s of the level, 128 coordinates (1 KB) per instruction, lane i
-    // supplying coordinates 2i and 2i+1. A level's wavefronts take the instructions in turn. Pairs beyond the
-    // last one (final iteration only) are redirected to the last pair and ignored later; coordinates beyond 2F
-    // read the following floats of the workspace (which is padded at its end for this) and land in the unused
-    // part of the staging area.
-    auto stage_direct = [&](int64_t pair0) {
+    // Staging: pair pair0 + s of level lvl goes to slot s of the wavefront, 128 coordinates (1 KB) per
+    // instruction, lane i supplying coordinates 2i and 2i+1. The wavefronts of a transform take the
+    // instructions in turn. Pairs beyond the last one (final group only) are redirected to the last pair and
+    // ignored later; coordinates beyond 2F read the following floats of the workspace (which is padded at its
+    // end for this) and land in the unused part of the staging area.
+    auto stage_direct = [&](int lvl, int64_t pair0) {
 #pragma unroll
         for (int s = 0; s < P::FPW; ++s) {
             const int64_t p = pair0 + s < pairs ? pair0 + s : pairs - 1;
-            const float *src = seq + p * pf + 4 * lane;
+            const float *src = seq + (int64_t)lvl * 2 * twoF + p * pf + 4 * lane;
             float2 *dst = wave_lds + s * PS;
             for (int j = sub; j < nload; j += P::WPL)
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + 256 * j),
@@ -378,165 +462,227 @@ __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
     // direct loads are issued before the recurrence arithmetic, which then runs under their latency.
     // (Measured: 3-4 % on D = 1024 and 2048 with five levels; with 32 float2 -- D = 512, four levels -- it no
     // longer pays, and loading the next iteration's table words early as well costs more registers than it hides.)
-    constexpr int ZREGS = P::FPW * BPT * M * 2;
+    constexpr int ZREGS = P::FPW * BPT * NTR * 2;
     constexpr bool kEarly = ZREGS <= 24;
     uint32_t gw[P::R], fw[kFoldInRegs];
-    // Tables of this level. They are the same every iteration and stay in L1/L2; the pointer is
-    // laundered so that the compiler reloads them every iteration instead of keeping ~90 loop-invariant
-    // registers (table words and everything derived from them) alive across the transform.
-    auto load_tables = [&]() {
-        const uint32_t *tabi = tab;
-        asm volatile("" : "+s"(tabi));
-#pragma unroll
-        for (int q = 0; q < P::R; ++q) gw[q] = tabi[tl.gather + lg + P::G * q];
-#pragma unroll
-        for (int g = 0; g < kFoldInRegs; ++g) fw[g] = g < NG ? tabi[tl.fold + g * P::GF + (lg % P::GF)] : kFoldPad << 16;
-    };
-    if (kEarly && pairs > 0) stage_direct(0);
-    for (int64_t pair0 = 0; pair0 < pairs; pair0 += P::FPW) {
-        const uint32_t *tabi = tab;
-        asm volatile("" : "+s"(tabi));
-        load_tables();
 
-        // 1a. staging
-        if (!kEarly) stage_direct(pair0);
-        __builtin_amdgcn_s_waitcnt(0x0f70);                 // vmcnt(0): the direct loads have landed
-        if ((T & 1) && pair0 + P::FPW >= pairs) {
-            // odd number of increments, last pair: its second step does not exist; what the producer left in
-            // its place (the increment across the sequence boundary) is cleared so that it cannot touch the result
-            float2 *st = wave_lds + (int)(pairs - 1 - pair0) * PS;
-            for (int a = sub * 64 + lane; a < twoF; a += 64 * P::WPL) st[a].y = 0.f;
-        }
-        transform_fence<P>();
-        // 1b. fold the third and later coordinates of a bucket into its first one, one rank per round
-        // (by the first wavefront of the level when a transform spans several)
-        auto fold = [&](uint32_t w) {
-            const uint32_t own = w & 0xffffu, tgt = w >> 16;
-            if (tgt != kFoldPad) {
-                const float2 x = *reinterpret_cast<const float2 *>(my_slot_bytes + own);
-                const float2 y = *reinterpret_cast<const float2 *>(my_slot_bytes + tgt);
-                *reinterpret_cast<float2 *>(my_slot_bytes + tgt) = make_float2(x.x + y.x, x.y + y.y);
+    // The item of this wavefront: level and pair group of its transform in the current iteration. Streaming:
+    // item number it * NTR + wv, counted (group, level) with the level running fastest.
+    int lvl = kStream ? wv % M : wv;
+    int64_t grp = kStream ? wv / M : 0;
+    auto advance = [&](int &l, int64_t &g) {                 // the same wavefront's item one iteration later
+        if constexpr (kStream) {
+            l += NTR % M;
+            g += NTR / M;
+            if (l >= M) {
+                l -= M;
+                ++g;
             }
-            wave_lds_fence();
-        };
-        if (sub == 0) {
-#pragma unroll
-            for (int g = 0; g < kFoldInRegs; ++g)
-                if (g < NG) fold(fw[g]);
-            for (int g = kFoldInRegs; g < NG; ++g) fold(tabi[tl.fold + g * P::GF + (lg % P::GF)]);
+        } else {
+            ++g;
         }
-        if constexpr (P::WPL > 1) __syncthreads();
-        // 1c. gather: first and second coordinate of each of this lane's buckets
-        float2 v[P::R];
+    };
+    // first item of the iteration (the one of wavefront 0)
+    int lvl0 = 0;
+    int64_t grp0 = 0;
+    LevelCarry<ORDER> carry[kStream ? P::FPW : 1][kStream ? BPT : 1];
+
+    if (kEarly && grp < groups) stage_direct(lvl, grp * P::FPW);
+    for (int64_t it = 0; it < iters; ++it) {
+        const int64_t pair0 = grp * P::FPW;
+        if (grp < groups) {                                  // streaming: the last iteration may have fewer items
+            // Tables of this level. They are the same whenever the level comes up and stay in L1/L2; the
+            // pointer is laundered so that the compiler reloads them every iteration instead of keeping ~90
+            // loop-invariant registers (table words and everything derived from them) alive across the transform.
+            const uint32_t *tabi = table + (int64_t)lvl * tl.words;
+            asm volatile("" : "+s"(tabi));
+            const int NG = kStream ? (int)tabi[0] : NG_fixed;
 #pragma unroll
-        for (int q = 0; q < P::R; ++q) {
-            const float2 x0 = *reinterpret_cast<const float2 *>(my_slot_bytes + (gw[q] & 0xffffu));
-            const float2 x1 = *reinterpret_cast<const float2 *>(my_slot_bytes + (gw[q] >> 16));
-            v[q] = make_float2(x0.x + x1.x, x0.y + x1.y);
-            // keep the scheduler from issuing all 2R reads at once (it would need 4R registers)
-            if (q % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+            for (int q = 0; q < P::R; ++q) gw[q] = tabi[tl.gather + lg + P::G * q];
+#pragma unroll
+            for (int g = 0; g < kFoldInRegs; ++g) fw[g] = g < NG ? tabi[tl.fold + g * P::GF + (lg % P::GF)] : kFoldPad << 16;
+
+            // 1a. staging
+            if (!kEarly) stage_direct(lvl, pair0);
+            __builtin_amdgcn_s_waitcnt(0x0f70);                 // vmcnt(0): the direct loads have landed
+            if ((T & 1) && pair0 + P::FPW >= pairs) {
+                // odd number of increments, last pair: its second step does not exist; what the producer left in
+                // its place (the increment across the sequence boundary) is cleared so that it cannot touch the result
+                float2 *st = wave_lds + (int)(pairs - 1 - pair0) * PS;
+                for (int a = sub * 64 + lane; a < twoF; a += 64 * P::WPL) st[a].y = 0.f;
+            }
+            transform_fence<P>();
+            // 1b. fold the third and later coordinates of a bucket into its first one, one rank per round
+            // (by the first wavefront of the transform when it spans several)
+            auto fold = [&](uint32_t w) {
+                const uint32_t own = w & 0xffffu, tgt = w >> 16;
+                if (tgt != kFoldPad) {
+                    const float2 x = *reinterpret_cast<const float2 *>(my_slot_bytes + own);
+                    const float2 y = *reinterpret_cast<const float2 *>(my_slot_bytes + tgt);
+                    *reinterpret_cast<float2 *>(my_slot_bytes + tgt) = make_float2(x.x + y.x, x.y + y.y);
+                }
+                wave_lds_fence();
+            };
+            if (sub == 0) {
+#pragma unroll
+                for (int g = 0; g < kFoldInRegs; ++g)
+                    if (g < NG) fold(fw[g]);
+                for (int g = kFoldInRegs; g < NG; ++g) fold(tabi[tl.fold + g * P::GF + (lg % P::GF)]);
+            }
+            if constexpr (P::WPL > 1) __syncthreads();
+            // 1c. gather: first and second coordinate of each of this lane's buckets
+            float2 v[P::R];
+#pragma unroll
+            for (int q = 0; q < P::R; ++q) {
+                const float2 x0 = *reinterpret_cast<const float2 *>(my_slot_bytes + (gw[q] & 0xffffu));
+                const float2 x1 = *reinterpret_cast<const float2 *>(my_slot_bytes + (gw[q] >> 16));
+                v[q] = make_float2(x0.x + x1.x, x0.y + x1.y);
+                // keep the scheduler from issuing all 2R reads at once (it would need 4R registers)
+                if (q % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+            }
+            // 2. FPW transforms per wavefront, in place in the slots
+            fft.run_from_registers(my_slot, v);
         }
-        // 2. FPW transforms per wavefront, in place in the slots
-        fft.run_from_registers(my_slot, v);
         __syncthreads();
-        // 3. per-bin separation and recurrence, two time steps per slot, levels ascending.
+        // 3. per-bin separation and recurrence, two time steps per slot, items in order (levels ascending
+        // within a pair).
         // For D = 1024 (128-register budget, one pair per wavefront) the thread index is laundered so that
         // the LDS addresses of the bins are recomputed here (a few adds) instead of being kept across the
         // whole iteration as loop invariants, where they were spilled to scratch (measured: 8 % faster
         // there, slower for the other transform lengths).
         int tid_here = tid;
         if constexpr (LOG2D == 10) asm volatile("" : "+v"(tid_here));
-        float2 zreg[kEarly ? P::FPW : 1][kEarly ? BPT : 1][kEarly ? M : 1][2];
+        float2 zreg[kEarly ? P::FPW : 1][kEarly ? BPT : 1][kEarly ? NTR : 1][2];
         if constexpr (kEarly) {
 #pragma unroll
             for (int s = 0; s < P::FPW; ++s)
 #pragma unroll
                 for (int b = 0; b < BPT; ++b) {
                     const int f = tid_here + NT * b;
-                    const int fi = pad(f < NB ? f : 0), fc = pad((D - (f < NB ? f : 0)) & (D - 1));
+                    const int fi = pad(f < NB ? f : 0), fc = pad(f > 0 && f < NB ? D - f : D / 2);
 #pragma unroll
-                    for (int l = 0; l < M; ++l) {
-                        const float2 *Z = lds + ((size_t)l * P::FPW + s) * PS;
-                        zreg[s][b][l][0] = Z[fi];
-                        zreg[s][b][l][1] = Z[fc];
+                    for (int j = 0; j < NTR; ++j) {
+                        const float2 *Z = lds + ((size_t)j * P::FPW + s) * PS;
+                        zreg[s][b][j][0] = Z[fi];
+                        zreg[s][b][j][1] = Z[fc];
                     }
                 }
             __syncthreads();                                        // the slots are free again
-            if (pair0 + P::FPW < pairs) stage_direct(pair0 + P::FPW);
         }
+        advance(lvl, grp);
+        if (kEarly && it + 1 < iters && grp < groups) stage_direct(lvl, grp * P::FPW);
+
+        // one (pair, level) of one bin: separation of the two steps and A_LL += ... for both
+        auto update_bin = [&](auto level_tag, auto packed_tag, int s, int b, int j, int64_t pair0_j, LevelCarry<ORDER> &c) {
+            constexpr int LL = decltype(level_tag)::value;
+            constexpr bool PK = decltype(packed_tag)::value != 0;      // this wavefront holds the thread of bins 0 and D/2
+            const int f = tid_here + NT * b;
+            if (f >= NB) return;
+            const bool pk = PK && f == 0;
+            auto mul = [&](float2 x, float2 y) { return PK ? cmulf_pk(x, y, pk) : cmulf(x, y); };
+            auto fma = [&](float2 x, float2 y, float2 w) { return PK ? cfmaf_pk(x, y, w, pk) : cfmaf(x, y, w); };
+            const bool second_step = 2 * (pair0_j + s) + 1 < T;    // wavefront-uniform
+            if constexpr (LL == 0) {
+                c.reset();
+                if (pk) c.p0.y = c.p1.y = 1.f;                          // A_0 = 1 in both bins of the packed thread
+            }
+            float2 z, zc;
+            if constexpr (kEarly) {
+                z = zreg[s][b][j][0];
+                zc = zreg[s][b][j][1];
+            } else {
+                const float2 *Z = lds + ((size_t)j * P::FPW + s) * PS;
+                z = Z[pad(f)];
+                zc = Z[pad(f > 0 ? D - f : D / 2)];
+            }
+            // separation of the two real transforms; for the packed thread z = Z[0], zc = Z[D/2] and
+            // C = (2 Re z, 2 Re zc), (2 Im z, 2 Im zc): the values the general formulas give at f = 0 and f = D/2
+            float2 C0 = make_float2(z.x + zc.x, z.y - zc.y);
+            // a second step that does not exist (odd number of increments) must contribute
+            // exactly nothing; the separation alone would leave rounding noise of the first
+            float2 C1 = make_float2(z.y + zc.y, zc.x - z.x);
+            if constexpr (PK) {
+                if (pk) {
+                    C0 = make_float2(z.x + z.x, zc.x + zc.x);
+                    C1 = make_float2(z.y + z.y, zc.y + zc.y);
+                }
+            }
+            if (!second_step) C1 = make_float2(0.f, 0.f);
+            const float2 a_old = A[b][LL];
+            float2 a_mid = fma(c.p0, C0, a_old);
+            // order >= 2 (a time step may be used up to `order` times in a row, q equal indices weighted
+            // 1/q!): also the values of levels l-2 (and l-3) before each step and the transforms of
+            // levels l-1 (and l-2) at both steps
+            float2 h0 = make_float2(0.f, 0.f), h1 = h0;
+            if constexpr (ORDER >= 2 && LL > 0) {
+                h0 = mul(c.c0p, C0);
+                a_mid = fma(make_float2(0.5f * c.q0.x, 0.5f * c.q0.y), h0, a_mid);
+            }
+            if constexpr (ORDER >= 3 && LL > 1) {
+                const float2 g = mul(c.c0pp, h0);
+                a_mid = fma(make_float2(c.r0.x * (1.0f / 6.0f), c.r0.y * (1.0f / 6.0f)), g, a_mid);
+            }
+            float2 a_new = fma(c.p1, C1, a_mid);
+            if constexpr (ORDER >= 2 && LL > 0) {
+                h1 = mul(c.c1p, C1);
+                a_new = fma(make_float2(0.5f * c.q1.x, 0.5f * c.q1.y), h1, a_new);
+            }
+            if constexpr (ORDER >= 3 && LL > 1) {
+                const float2 g = mul(c.c1pp, h1);
+                a_new = fma(make_float2(c.r1.x * (1.0f / 6.0f), c.r1.y * (1.0f / 6.0f)), g, a_new);
+            }
+            if constexpr (ORDER >= 3) {
+                c.r0 = c.q0;
+                c.r1 = c.q1;
+                c.c0pp = c.c0p;
+                c.c1pp = c.c1p;
+            }
+            if constexpr (ORDER >= 2) {
+                c.q0 = c.p0;
+                c.q1 = c.p1;
+                c.c0p = C0;
+                c.c1p = C1;
+            }
+            A[b][LL] = a_new;
+            c.p0 = a_old;
+            c.p1 = a_mid;
+        };
+        auto update = [&](auto level_tag, int s, int b, int j, int64_t pair0_j, LevelCarry<ORDER> &c) {
+            if (b == 0 && wave == 0) update_bin(level_tag, LevelTag<1>{}, s, b, j, pair0_j, c);
+            else update_bin(level_tag, LevelTag<0>{}, s, b, j, pair0_j, c);
+        };
+        if constexpr (kStream) {
+            // one branch on the level of the iteration's first item; inside it every item's level is static
+            with_level<M>(lvl0, [&](auto first_tag) {
+                constexpr int L0 = decltype(first_tag)::value;
+                item_loop<L0, M, NTR>([&](auto level_tag, auto item_tag, int group_offset) {
+                        constexpr int j = decltype(item_tag)::value;
+                        const int64_t g = grp0 + group_offset;
+                        if (g < groups) {
+                            const int64_t pair0_j = g * P::FPW;
 #pragma unroll
-        for (int s = 0; s < P::FPW; ++s) {
-            const bool second_step = 2 * (pair0 + s) + 1 < T;      // wavefront-uniform
-            if (pair0 + s >= pairs) continue;                       // slot without a pair (last iteration only)
+                            for (int s = 0; s < P::FPW; ++s) {
+                                if (pair0_j + s >= pairs) continue;     // slot without a pair (last group only)
 #pragma unroll
-            for (int b = 0; b < BPT; ++b) {
-                const int f = tid_here + NT * b;
-                if (f < NB) {
-                    const int fi = pad(f), fc = pad((D - f) & (D - 1));
-                    float2 p0 = make_float2(1.f, 0.f), p1 = make_float2(1.f, 0.f);
-                    // order >= 2 (a time step may be used up to `order` times in a row, q equal indices weighted
-                    // 1/q!): also the values of levels l-2 (and l-3) before each step and the transforms of
-                    // levels l-1 (and l-2) at both steps
-                    float2 q0 = make_float2(0.f, 0.f), q1 = q0, c0p = q0, c1p = q0;
-                    float2 r0 = q0, r1 = q0, c0pp = q0, c1pp = q0;
+                                for (int b = 0; b < BPT; ++b) update(level_tag, s, b, j, pair0_j, carry[s][b]);
+                            }
+                        }
+                });
+            });
+            lvl0 += NTR % M;
+            grp0 += NTR / M;
+            if (lvl0 >= M) {
+                lvl0 -= M;
+                ++grp0;
+            }
+        } else {
 #pragma unroll
-                    for (int l = 0; l < M; ++l) {
-                        const float2 *Z = lds + ((size_t)l * P::FPW + s) * PS;
-                        float2 z, zc;
-                        if constexpr (kEarly) {
-                            z = zreg[s][b][l][0];
-                            zc = zreg[s][b][l][1];
-                        } else {
-                            z = Z[fi];
-                            zc = Z[fc];
-                        }
-                        const float2 C0 = make_float2(z.x + zc.x, z.y - zc.y);
-                        // a second step that does not exist (odd number of increments) must contribute
-                        // exactly nothing; the separation alone would leave rounding noise of the first
-                        float2 C1 = make_float2(z.y + zc.y, zc.x - z.x);
-                        if (!second_step) C1 = make_float2(0.f, 0.f);
-                        const float2 a_old = A[b][l];
-                        float2 a_mid = cfmaf(p0, C0, a_old);
-                        float2 h0 = make_float2(0.f, 0.f), h1 = h0;
-                        if constexpr (ORDER >= 2) {
-                            if (l > 0) {
-                                h0 = cmulf(c0p, C0);
-                                a_mid = cfmaf(make_float2(0.5f * q0.x, 0.5f * q0.y), h0, a_mid);
-                            }
-                        }
-                        if constexpr (ORDER >= 3) {
-                            if (l > 1) {
-                                const float2 g = cmulf(c0pp, h0);
-                                a_mid = cfmaf(make_float2(r0.x * (1.0f / 6.0f), r0.y * (1.0f / 6.0f)), g, a_mid);
-                            }
-                        }
-                        float2 a_new = cfmaf(p1, C1, a_mid);
-                        if constexpr (ORDER >= 2) {
-                            if (l > 0) {
-                                h1 = cmulf(c1p, C1);
-                                a_new = cfmaf(make_float2(0.5f * q1.x, 0.5f * q1.y), h1, a_new);
-                            }
-                        }
-                        if constexpr (ORDER >= 3) {
-                            if (l > 1) {
-                                const float2 g = cmulf(c1pp, h1);
-                                a_new = cfmaf(make_float2(r1.x * (1.0f / 6.0f), r1.y * (1.0f / 6.0f)), g, a_new);
-                            }
-                            r0 = q0;
-                            r1 = q1;
-                            c0pp = c0p;
-                            c1pp = c1p;
-                        }
-                        if constexpr (ORDER >= 2) {
-                            q0 = p0;
-                            q1 = p1;
-                            c0p = C0;
-                            c1p = C1;
-                        }
-                        A[b][l] = a_new;
-                        p0 = a_old;
-                        p1 = a_mid;
-                    }
+            for (int s = 0; s < P::FPW; ++s) {
+                if (pair0 + s >= pairs) continue;                       // slot without a pair (last iteration only)
+#pragma unroll
+                for (int b = 0; b < BPT; ++b) {
+                    LevelCarry<ORDER> c;
+                    level_loop<M>([&](auto level_tag) { update(level_tag, s, b, decltype(level_tag)::value, pair0, c); });
                 }
             }
         }
@@ -544,7 +690,7 @@ __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
     }
     if (kEarly) __syncthreads();
 
-    // Phi_m = Re(FFT(conj Y_m)) / D with Y_m the Hermitian extension of A_m; slot 0 of wavefront m.
+    // Phi_m = Re(FFT(conj Y_m)) / D with Y_m the Hermitian extension of A_m; slot 0 of transform m of the workgroup.
 #pragma unroll
     for (int b = 0; b < BPT; ++b) {
         const int f = tid + NT * b;
@@ -553,24 +699,31 @@ __global__ __launch_bounds__(64 * M * Plan<LOG2D>::WPL)
             for (int l = 0; l < M; ++l) {
                 float2 *Y = lds + (size_t)l * P::FPW * PS;
                 const float2 y = A[b][l];
-                Y[pad(f)] = make_float2(y.x, -y.y);
-                if (f > 0 && f < D / 2) Y[pad(D - f)] = y;
+                if (f > 0) {
+                    Y[pad(f)] = make_float2(y.x, -y.y);
+                    Y[pad(D - f)] = y;
+                } else {                                     // bins 0 and D/2, both real
+                    Y[pad(0)] = make_float2(y.x, 0.f);
+                    Y[pad(D / 2)] = make_float2(y.y, 0.f);
+                }
             }
         }
     }
     __syncthreads();
-    fft.run(my_slot);
-    transform_fence<P>();
-    float *row = out + n * ld_out;
-    if (tid == 0) row[0] = 1.0f;
-    const float invD = 1.0f / (float)D;
-    // Dout buckets per level. Dout == D: the transform was circular in D already. Dout < D (a bucket
-    // count that is no power of two): D was chosen so large that the M-fold convolution never wrapped,
-    // and the linear result is folded modulo Dout here.
-    for (int j = sub * 64 + lane; j < Dout; j += 64 * P::WPL) {
-        float acc = 0.f;
-        for (int e = j; e < D; e += Dout) acc += wave_lds[pad(e)].x;
-        row[1 + (int64_t)m * Dout + j] = acc * invD;
+    if (wv < M) {                                            // (always, unless streaming)
+        fft.run(my_slot);
+        transform_fence<P>();
+        float *row = out + n * ld_out;
+        if (tid == 0) row[0] = 1.0f;
+        const float invD = 1.0f / (float)D;
+        // Dout buckets per level. Dout == D: the transform was circular in D already. Dout < D (a bucket
+        // count that is no power of two): D was chosen so large that the M-fold convolution never wrapped,
+        // and the linear result is folded modulo Dout here.
+        for (int j = sub * 64 + lane; j < Dout; j += 64 * P::WPL) {
+            float acc = 0.f;
+            for (int e = j; e < D; e += Dout) acc += wave_lds[pad(e)].x;
+            row[1 + (int64_t)wv * Dout + j] = acc * invD;
+        }
     }
 }
 
