@@ -272,8 +272,9 @@ size_t sketch_fft_scan_lds_bytes(int M, int F, int D)
 {
     TunedGeometry g;
     if (!tuned_geometry(D, &g)) return 0;
-    const int wpl = D > 1024 ? D / 1024 : 1;             // wavefronts per transform
-    return sizeof(float2) * ((size_t)tuned::transforms_in_flight(M, wpl) * g.FPW * tuned::slot_stride(g.PD, 2 * F) + g.NTWL);
+    int log2d = 0;
+    while ((1 << log2d) < D) ++log2d;
+    return sizeof(float2) * ((size_t)tuned::transforms_in_flight(M, log2d) * g.FPW * tuned::slot_stride(g.PD, 2 * F) + g.NTWL);
 }
 
 bool sketch_fft_scan_is_tuned(int M, int F, int D)

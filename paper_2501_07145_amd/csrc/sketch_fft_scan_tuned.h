@@ -326,13 +326,15 @@ struct WaveFft {
 };
 
 // Number of transforms a workgroup has in flight per iteration (= its wavefronts when a transform lives in one
-// wavefront). Normally one per level. With 5, 6 or 7 levels that would make workgroups of 5-7 wavefronts, and
-// the hardware then keeps far fewer of them resident than registers and LDS allow (measured with an empty
-// kernel of the same footprint, ~116 registers and 51 KB: 1.7 workgroups = 8.6 wavefronts per CU for 5
-// wavefronts per workgroup, 15.6 wavefronts for 4 or 8 per workgroup: the dispatcher reserves registers for
-// ceil(wavefronts / 4) wavefronts on every SIMD). Those level counts therefore run 8 wavefronts that take the
-// (pair, level) transforms of the sequence in order, 8 at a time, whatever level they belong to.
-__host__ __device__ constexpr int transforms_in_flight(int M, int WPL) { return (WPL == 1 && M >= 5 && M <= 7) ? 8 : M; }
+// wavefront). Normally one per level. With 5 or 6 levels that makes workgroups of 5 or 6 wavefronts, and the
+// hardware then keeps far fewer of them resident than registers and LDS allow (measured with an empty kernel
+// of the same footprint, ~116 registers and 51 KB: 1.7 workgroups = 8.6 wavefronts per CU for 5 wavefronts per
+// workgroup, 15.6 wavefronts for 4 or 8 per workgroup: the dispatcher reserves registers for
+// ceil(wavefronts / 4) wavefronts on every SIMD). For D = 1024 those level counts therefore run 8 wavefronts
+// that take the (pair, level) transforms of the sequence in order, 8 at a time, whatever level they belong to.
+// (Measured against one wavefront per level at 100 steps: D = 1024 +10 % with 5 levels, +23 % with 6, -9 % with
+// 7; D = 512 +-1 %; D <= 256, where a wavefront carries four or more transforms, 35-60 % slower.)
+__host__ __device__ constexpr int transforms_in_flight(int M, int LOG2D) { return (LOG2D == 10 && (M == 5 || M == 6)) ? 8 : M; }
 
 template <int LL>
 struct LevelTag {
@@ -398,10 +400,16 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
     // may end in the middle of a pair; otherwise transform w of the workgroup is always level w.
     constexpr bool kStream = NTR != M;
     static_assert(!kStream || (P::WPL == 1 && NTR > M), "streaming needs one wavefront per transform and a slot per level");
-    // Bins of phase 3: f = 0 .. D/2 - 1, thread t owning f = t, t + NT, ... The transforms of real sequences are
-    // real at f = 0 and f = D/2; thread 0 carries both in one float2 (bin 0 in .x, bin D/2 in .y), which keeps the
-    // number of bins a power of two.
-    constexpr int D = P::D, NT = 64 * NTR * P::WPL, NB = D / 2, BPT = (NB + NT - 1) / NT;
+    // Bins of phase 3: f = 0 .. D/2, thread t owning f = t, t + NT, ... The transforms of real sequences are real
+    // at f = 0 and f = D/2. Where that saves a bin per thread (NT divides D/2), thread 0 carries both in one
+    // float2 (bin 0 in .x, bin D/2 in .y; kPack) and the bins are f = 0 .. D/2 - 1.
+    constexpr int D = P::D, NT = 64 * NTR * P::WPL;
+    constexpr bool kPack = (D / 2) % NT == 0;
+    constexpr int NB = kPack ? D / 2 : D / 2 + 1, BPT = (NB + NT - 1) / NT;
+    // Phase 3 is compiled separately for iterations in which every item exists and has both time steps (no
+    // per-item conditions and selects) when a wavefront has at most two transforms per iteration; with more the
+    // extra copy costs registers.
+    constexpr bool kSplitFull = P::FPW <= 2;
     extern __shared__ float2 lds[];                    // [NTR][FPW][PS] slots, then the twiddle table
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wv = wave / P::WPL, sub = wave % P::WPL;       // transform of the workgroup, wavefront within it
@@ -419,15 +427,16 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
     const int64_t Ln = lengths ? (lengths[n] < 1 ? 1 : (lengths[n] > L ? L : lengths[n])) : L;
     const int64_t T = Ln - 1;
     const int64_t pairs = (T + 1) / 2;
-    const int64_t groups = (pairs + P::FPW - 1) / P::FPW;    // a transform carries FPW consecutive pairs of one level
-    const int64_t iters = kStream ? (groups * M + NTR - 1) / NTR : groups;
     // pair p of level l: 2F float2 at seq + l * 2 * twoF + p * pf (pair layout of the producing kernel, Lp / 2
     // pair slots per sequence with Lp = L rounded up to even)
     const int64_t pf = (int64_t)M * 2 * twoF;
     const float *seq = dphi + n * ((L + 1) / 2) * pf;
     const TableLayout tl = table_layout(D, P::GF, twoF);
     const int nload = staged(twoF) / 128;                    // direct loads per pair, 128 coordinates each
-    const int NG_fixed = kStream ? 0 : (int)table[(int64_t)wv * tl.words];   // fold rounds of the wavefront's fixed level
+    // one level per wavefront for good: its increments, table and number of fold rounds
+    const float *seq_fixed = seq + (int64_t)wv * 2 * twoF;
+    const uint32_t *tab_fixed = table + (int64_t)wv * tl.words;
+    const int NG_fixed = kStream ? 0 : (int)tab_fixed[0];
 
     WaveFft<P> fft;
     fft.init(lg, twl_table);
@@ -449,7 +458,7 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
 #pragma unroll
         for (int s = 0; s < P::FPW; ++s) {
             const int64_t p = pair0 + s < pairs ? pair0 + s : pairs - 1;
-            const float *src = seq + (int64_t)lvl * 2 * twoF + p * pf + 4 * lane;
+            const float *src = (kStream ? seq + (int64_t)lvl * 2 * twoF : seq_fixed) + p * pf + 4 * lane;
             float2 *dst = wave_lds + s * PS;
             for (int j = sub; j < nload; j += P::WPL)
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + 256 * j),
@@ -466,35 +475,36 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
     constexpr bool kEarly = ZREGS <= 24;
     uint32_t gw[P::R], fw[kFoldInRegs];
 
-    // The item of this wavefront: level and pair group of its transform in the current iteration. Streaming:
-    // item number it * NTR + wv, counted (group, level) with the level running fastest.
+    // The item of this wavefront: level and first pair of its transform in the current iteration (a transform
+    // carries FPW consecutive pairs of one level, a pair group). Streaming: the items of the sequence are counted
+    // (group, level) with the level running fastest, and this wavefront has number iteration * NTR + wv.
     int lvl = kStream ? wv % M : wv;
-    int64_t grp = kStream ? wv / M : 0;
-    auto advance = [&](int &l, int64_t &g) {                 // the same wavefront's item one iteration later
+    int64_t pair0 = kStream ? (wv / M) * P::FPW : 0;
+    auto advance = [&](int &l, int64_t &p0) {                // the same wavefront's item one iteration later
         if constexpr (kStream) {
             l += NTR % M;
-            g += NTR / M;
+            p0 += (NTR / M) * P::FPW;
             if (l >= M) {
                 l -= M;
-                ++g;
+                p0 += P::FPW;
             }
         } else {
-            ++g;
+            p0 += P::FPW;
         }
     };
-    // first item of the iteration (the one of wavefront 0)
-    int lvl0 = 0;
-    int64_t grp0 = 0;
+    // first item of the iteration (the one of wavefront 0; streaming only)
+    int lvl_first = 0;
+    int64_t pair0_first = 0;
     LevelCarry<ORDER> carry[kStream ? P::FPW : 1][kStream ? BPT : 1];
 
-    if (kEarly && grp < groups) stage_direct(lvl, grp * P::FPW);
-    for (int64_t it = 0; it < iters; ++it) {
-        const int64_t pair0 = grp * P::FPW;
-        if (grp < groups) {                                  // streaming: the last iteration may have fewer items
+    if (kEarly && pair0 < pairs) stage_direct(lvl, pair0);
+    // an iteration exists while its first item does
+    while ((kStream ? pair0_first : pair0) < pairs) {
+        if (!kStream || pair0 < pairs) {                      // streaming: the last iteration may have fewer items
             // Tables of this level. They are the same whenever the level comes up and stay in L1/L2; the
             // pointer is laundered so that the compiler reloads them every iteration instead of keeping ~90
             // loop-invariant registers (table words and everything derived from them) alive across the transform.
-            const uint32_t *tabi = table + (int64_t)lvl * tl.words;
+            const uint32_t *tabi = kStream ? table + (int64_t)lvl * tl.words : tab_fixed;
             asm volatile("" : "+s"(tabi));
             const int NG = kStream ? (int)tabi[0] : NG_fixed;
 #pragma unroll
@@ -559,7 +569,8 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
 #pragma unroll
                 for (int b = 0; b < BPT; ++b) {
                     const int f = tid_here + NT * b;
-                    const int fi = pad(f < NB ? f : 0), fc = pad(f > 0 && f < NB ? D - f : D / 2);
+                    const int fi = pad(f < NB ? f : 0);
+                    const int fc = kPack ? pad(f > 0 && f < NB ? D - f : D / 2) : pad((D - (f < NB ? f : 0)) & (D - 1));
 #pragma unroll
                     for (int j = 0; j < NTR; ++j) {
                         const float2 *Z = lds + ((size_t)j * P::FPW + s) * PS;
@@ -569,19 +580,21 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
                 }
             __syncthreads();                                        // the slots are free again
         }
-        advance(lvl, grp);
-        if (kEarly && it + 1 < iters && grp < groups) stage_direct(lvl, grp * P::FPW);
+        const int64_t pair0_now = pair0;
+        advance(lvl, pair0);
+        if (kEarly && pair0 < pairs) stage_direct(lvl, pair0);
 
         // one (pair, level) of one bin: separation of the two steps and A_LL += ... for both
-        auto update_bin = [&](auto level_tag, auto packed_tag, int s, int b, int j, int64_t pair0_j, LevelCarry<ORDER> &c) {
+        auto update_bin = [&](auto level_tag, auto packed_tag, auto full_tag, int s, int b, int j, int64_t pair0_j,
+                              LevelCarry<ORDER> &c) {
             constexpr int LL = decltype(level_tag)::value;
-            constexpr bool PK = decltype(packed_tag)::value != 0;      // this wavefront holds the thread of bins 0 and D/2
-            const int f = tid_here + NT * b;
-            if (f >= NB) return;
-            const bool pk = PK && f == 0;
+            constexpr bool PK = kPack && decltype(packed_tag)::value != 0;   // this wavefront holds the thread of bins 0 and D/2
+            constexpr bool FULL = decltype(full_tag)::value != 0;      // every item of the iteration has both steps
+            const int f = tid_here + NT * b;                            // a bin that exists (the caller checks)
+            const bool pk = PK && b == 0 && f == 0;
             auto mul = [&](float2 x, float2 y) { return PK ? cmulf_pk(x, y, pk) : cmulf(x, y); };
             auto fma = [&](float2 x, float2 y, float2 w) { return PK ? cfmaf_pk(x, y, w, pk) : cfmaf(x, y, w); };
-            const bool second_step = 2 * (pair0_j + s) + 1 < T;    // wavefront-uniform
+            const bool second_step = FULL || 2 * (pair0_j + s) + 1 < T;    // wavefront-uniform
             if constexpr (LL == 0) {
                 c.reset();
                 if (pk) c.p0.y = c.p1.y = 1.f;                          // A_0 = 1 in both bins of the packed thread
@@ -593,7 +606,7 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
             } else {
                 const float2 *Z = lds + ((size_t)j * P::FPW + s) * PS;
                 z = Z[pad(f)];
-                zc = Z[pad(f > 0 ? D - f : D / 2)];
+                zc = Z[kPack ? pad(f > 0 ? D - f : D / 2) : pad((D - f) & (D - 1))];
             }
             // separation of the two real transforms; for the packed thread z = Z[0], zc = Z[D/2] and
             // C = (2 Re z, 2 Re zc), (2 Im z, 2 Im zc): the values the general formulas give at f = 0 and f = D/2
@@ -647,45 +660,57 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
             c.p0 = a_old;
             c.p1 = a_mid;
         };
-        auto update = [&](auto level_tag, int s, int b, int j, int64_t pair0_j, LevelCarry<ORDER> &c) {
-            if (b == 0 && wave == 0) update_bin(level_tag, LevelTag<1>{}, s, b, j, pair0_j, c);
-            else update_bin(level_tag, LevelTag<0>{}, s, b, j, pair0_j, c);
-        };
-        if constexpr (kStream) {
-            // one branch on the level of the iteration's first item; inside it every item's level is static
-            with_level<M>(lvl0, [&](auto first_tag) {
-                constexpr int L0 = decltype(first_tag)::value;
-                item_loop<L0, M, NTR>([&](auto level_tag, auto item_tag, int group_offset) {
+        // The whole of phase 3, compiled four times: for the wavefront of the packed thread and for the others,
+        // and for iterations whose items all exist and have both time steps (all but the last one or two of a
+        // sequence: no per-item conditions, no selects) and for the rest.
+        auto phase3 = [&](auto packed_tag, auto full_tag) {
+            constexpr bool FULL = decltype(full_tag)::value != 0;
+            if constexpr (kStream) {
+                // one branch on the level of the iteration's first item; inside it every item's level is static
+                with_level<M>(lvl_first, [&](auto first_tag) {
+                    constexpr int L0 = decltype(first_tag)::value;
+                    item_loop<L0, M, NTR>([&](auto level_tag, auto item_tag, int group_offset) {
                         constexpr int j = decltype(item_tag)::value;
-                        const int64_t g = grp0 + group_offset;
-                        if (g < groups) {
-                            const int64_t pair0_j = g * P::FPW;
+                        const int64_t pair0_j = pair0_first + group_offset * P::FPW;
+                        if (FULL || pair0_j < pairs) {
 #pragma unroll
                             for (int s = 0; s < P::FPW; ++s) {
-                                if (pair0_j + s >= pairs) continue;     // slot without a pair (last group only)
+                                if (!FULL && pair0_j + s >= pairs) continue;   // slot without a pair (last group only)
 #pragma unroll
-                                for (int b = 0; b < BPT; ++b) update(level_tag, s, b, j, pair0_j, carry[s][b]);
+                                for (int b = 0; b < BPT; ++b)
+                                    if (NT * BPT == NB || tid_here + NT * b < NB)
+                                        update_bin(level_tag, packed_tag, full_tag, s, b, j, pair0_j, carry[s][b]);
                             }
                         }
+                    });
                 });
-            });
-            lvl0 += NTR % M;
-            grp0 += NTR / M;
-            if (lvl0 >= M) {
-                lvl0 -= M;
-                ++grp0;
-            }
-        } else {
+            } else {
 #pragma unroll
-            for (int s = 0; s < P::FPW; ++s) {
-                if (pair0 + s >= pairs) continue;                       // slot without a pair (last iteration only)
+                for (int s = 0; s < P::FPW; ++s) {
+                    if (!FULL && pair0_now + s >= pairs) continue;             // slot without a pair (last iteration only)
 #pragma unroll
-                for (int b = 0; b < BPT; ++b) {
-                    LevelCarry<ORDER> c;
-                    level_loop<M>([&](auto level_tag) { update(level_tag, s, b, decltype(level_tag)::value, pair0, c); });
+                    for (int b = 0; b < BPT; ++b) {
+                        if (NT * BPT == NB || tid_here + NT * b < NB) {
+                            LevelCarry<ORDER> c;
+                            level_loop<M>([&](auto level_tag) {
+                                update_bin(level_tag, packed_tag, full_tag, s, b, decltype(level_tag)::value, pair0_now, c);
+                            });
+                        }
+                    }
                 }
             }
+        };
+        // full: the last pair of the last pair group that this iteration touches has a second step
+        const int64_t last_pair0 = kStream ? pair0_first + ((lvl_first + NTR - 1) / M) * P::FPW : pair0_now;
+        const bool full = 2 * (last_pair0 + P::FPW) - 1 < T;
+        if (kPack && wave == 0) {
+            if (kSplitFull && full) phase3(LevelTag<1>{}, LevelTag<1>{});
+            else phase3(LevelTag<1>{}, LevelTag<0>{});
+        } else {
+            if (kSplitFull && full) phase3(LevelTag<0>{}, LevelTag<1>{});
+            else phase3(LevelTag<0>{}, LevelTag<0>{});
         }
+        if constexpr (kStream) advance(lvl_first, pair0_first);
         if (!kEarly) __syncthreads();
     }
     if (kEarly) __syncthreads();
@@ -699,12 +724,12 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
             for (int l = 0; l < M; ++l) {
                 float2 *Y = lds + (size_t)l * P::FPW * PS;
                 const float2 y = A[b][l];
-                if (f > 0) {
-                    Y[pad(f)] = make_float2(y.x, -y.y);
-                    Y[pad(D - f)] = y;
-                } else {                                     // bins 0 and D/2, both real
+                if (kPack && f == 0) {                       // bins 0 and D/2, both real
                     Y[pad(0)] = make_float2(y.x, 0.f);
                     Y[pad(D / 2)] = make_float2(y.y, 0.f);
+                } else {
+                    Y[pad(f)] = make_float2(y.x, -y.y);
+                    if (f > 0 && f < D / 2) Y[pad(D - f)] = y;
                 }
             }
         }
