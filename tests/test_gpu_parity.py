@@ -308,6 +308,36 @@ def test_signature_order_three(oracle, N, L, d, M, F, D):
         assert e.value.code == -9
 
 
+@pytest.mark.parametrize("L", [2, 3, 4, 5, 6, 7, 10, 17])
+@pytest.mark.parametrize("M,order", [(5, 1), (6, 1), (5, 2), (6, 3)])
+def test_levels_dealt_to_eight_wavefronts(oracle, L, M, order):
+    """Transforms of 1024 with 5 or 6 levels: the (pair, level) items go to eight wavefronts in order, so a pair
+    may be split between iterations and the last iteration has between one and eight items. The lengths cover
+    every remainder of pairs * M modulo 8 for both level counts, with odd and even numbers of increments; each
+    case also runs with a bucket count of 200 (M = 5: linear convolution in a transform of 1024) and as a
+    batch of different lengths."""
+    N, d, F, D = 6, 3, 48, 1024
+    inp = _random_case(700 + L + 10 * M, N, L, d, M, F, D)
+    got = _gpu_features(inp, D, order=order).cpu().numpy()
+    want = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D, order=order)
+    err = block_errors(got, want, M, D)
+    print(f"L={L} M={M} order {order}: block errors", err)
+    assert np.all(err <= FP32_BLOCK_TOL)
+    lengths = np.array([L, 1, max(1, L - 1), max(1, L // 2), 2, max(1, L - 2)])
+    t = _dev(inp)
+    got_r = rfsf.rfsf_ts_features(t["X"], t["W"], t["hash"], t["sign"], inp["lengthscale"], D, order=order,
+                                  lengths=torch.from_numpy(lengths).cuda()).cpu().numpy()
+    want_r = oracle.features_ragged(inp["X"], lengths, inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D,
+                                    order=order)
+    assert np.all(block_errors(got_r, want_r, M, D) <= FP32_BLOCK_TOL)
+    if M == 5:
+        D2 = 200
+        inp2 = _random_case(800 + L, N, L, d, M, F, D2)
+        got2 = _gpu_features(inp2, D2, order=order).cpu().numpy()
+        want2 = oracle.features(inp2["X"], inp2["W"], inp2["hash"], inp2["sign"], inp2["lengthscale"], D2, order=order)
+        assert np.all(block_errors(got2, want2, M, D2) <= FP32_BLOCK_TOL)
+
+
 @pytest.mark.parametrize("N,L,d,M,F,D,order", [
     (9, 33, 3, 3, 32, 64, 1),       # several pairs per wavefront
     (7, 20, 4, 5, 64, 1024, 1),     # one pair per wavefront
