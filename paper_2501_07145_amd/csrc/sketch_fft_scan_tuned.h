@@ -497,6 +497,7 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
     int64_t pair0_first = 0;
     LevelCarry<ORDER> carry[kStream ? P::FPW : 1][kStream ? BPT : 1];
 
+    __builtin_amdgcn_s_setprio(1);
     if (kEarly && pair0 < pairs) stage_direct(lvl, pair0);
     // an iteration exists while its first item does
     while ((kStream ? pair0_first : pair0) < pairs) {
@@ -550,8 +551,14 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
                 // keep the scheduler from issuing all 2R reads at once (it would need 4R registers)
                 if (q % 4 == 3) __builtin_amdgcn_sched_barrier(0);
             }
-            // 2. FPW transforms per wavefront, in place in the slots
+            // 2. FPW transforms per wavefront, in place in the slots. The transform is the one long stretch of
+            // arithmetic of an iteration; everything else is short pieces of work between waits (loads, LDS round
+            // trips, barriers). A wavefront in those phases runs at a raised priority, so that it gets its few
+            // instructions issued at once and goes back to waiting instead of queueing behind other wavefronts'
+            // transforms (measured: 3-7 % on every workload; the other way round, 2-3 % slower).
+            __builtin_amdgcn_s_setprio(0);
             fft.run_from_registers(my_slot, v);
+            __builtin_amdgcn_s_setprio(1);
         }
         __syncthreads();
         // 3. per-bin separation and recurrence, two time steps per slot, items in order (levels ascending
