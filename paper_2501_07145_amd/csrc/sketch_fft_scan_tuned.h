@@ -336,6 +336,8 @@ struct WaveFft {
 // 7; D = 512 +-1 %; D <= 256, where a wavefront carries four or more transforms, 35-60 % slower.)
 __host__ __device__ constexpr int transforms_in_flight(int M, int LOG2D) { return (LOG2D == 10 && (M == 5 || M == 6)) ? 8 : M; }
 
+typedef const __attribute__((address_space(1))) uint32_t *GlobalWords;   // table words, known to be in global memory
+
 template <int LL>
 struct LevelTag {
     static constexpr int value = LL;
@@ -386,6 +388,72 @@ __device__ __forceinline__ void level_loop(Fn &&f)
         f(LevelTag<LL>{});
         level_loop<M, LL + 1>(f);
     }
+}
+
+// One level of one pair of time steps at one bin (Sec. 3.5 eq. (ts_rec)): z and zc are the transform of the
+// level's slot at the bin and at its mirror image; separates the two real transforms and advances the bin's
+// accumulator a = A_LL by both steps, c carrying what level LL - 1 of the same pair left. PK: the thread may be
+// the packed one (pk), whose float2 hold bins 0 and D/2 and whose z, zc are Z[0], Z[D/2].
+template <int ORDER, int LL, bool PK>
+__device__ __forceinline__ void level_step(float2 z, float2 zc, bool pk, bool second_step, float2 &a, LevelCarry<ORDER> &c)
+{
+    auto mul = [&](float2 x, float2 y) { return PK ? cmulf_pk(x, y, pk) : cmulf(x, y); };
+    auto fma = [&](float2 x, float2 y, float2 w) { return PK ? cfmaf_pk(x, y, w, pk) : cfmaf(x, y, w); };
+    if constexpr (LL == 0) {
+        c.reset();
+        if (PK && pk) c.p0.y = c.p1.y = 1.f;                            // A_0 = 1 in both bins of the packed thread
+    }
+    // separation of the two real transforms; for the packed thread C = (2 Re z, 2 Re zc), (2 Im z, 2 Im zc):
+    // the values the general formulas give at f = 0 and f = D/2
+    float2 C0 = make_float2(z.x + zc.x, z.y - zc.y);
+    // a second step that does not exist (odd number of increments) must contribute
+    // exactly nothing; the separation alone would leave rounding noise of the first
+    float2 C1 = make_float2(z.y + zc.y, zc.x - z.x);
+    if constexpr (PK) {
+        if (pk) {
+            C0 = make_float2(z.x + z.x, zc.x + zc.x);
+            C1 = make_float2(z.y + z.y, zc.y + zc.y);
+        }
+    }
+    if (!second_step) C1 = make_float2(0.f, 0.f);
+    const float2 a_old = a;
+    float2 a_mid = fma(c.p0, C0, a_old);
+    // order >= 2 (a time step may be used up to `order` times in a row, q equal indices weighted
+    // 1/q!): also the values of levels l-2 (and l-3) before each step and the transforms of
+    // levels l-1 (and l-2) at both steps
+    float2 h0 = make_float2(0.f, 0.f), h1 = h0;
+    if constexpr (ORDER >= 2 && LL > 0) {
+        h0 = mul(c.c0p, C0);
+        a_mid = fma(make_float2(0.5f * c.q0.x, 0.5f * c.q0.y), h0, a_mid);
+    }
+    if constexpr (ORDER >= 3 && LL > 1) {
+        const float2 g = mul(c.c0pp, h0);
+        a_mid = fma(make_float2(c.r0.x * (1.0f / 6.0f), c.r0.y * (1.0f / 6.0f)), g, a_mid);
+    }
+    float2 a_new = fma(c.p1, C1, a_mid);
+    if constexpr (ORDER >= 2 && LL > 0) {
+        h1 = mul(c.c1p, C1);
+        a_new = fma(make_float2(0.5f * c.q1.x, 0.5f * c.q1.y), h1, a_new);
+    }
+    if constexpr (ORDER >= 3 && LL > 1) {
+        const float2 g = mul(c.c1pp, h1);
+        a_new = fma(make_float2(c.r1.x * (1.0f / 6.0f), c.r1.y * (1.0f / 6.0f)), g, a_new);
+    }
+    if constexpr (ORDER >= 3) {
+        c.r0 = c.q0;
+        c.r1 = c.q1;
+        c.c0pp = c.c0p;
+        c.c1pp = c.c1p;
+    }
+    if constexpr (ORDER >= 2) {
+        c.q0 = c.p0;
+        c.q1 = c.p1;
+        c.c0p = C0;
+        c.c1p = C1;
+    }
+    a = a_new;
+    c.p0 = a_old;
+    c.p1 = a_mid;
 }
 
 template <int LOG2D, int M, int ORDER, int NTR>
@@ -505,8 +573,10 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
             // Tables of this level. They are the same whenever the level comes up and stay in L1/L2; the
             // pointer is laundered so that the compiler reloads them every iteration instead of keeping ~90
             // loop-invariant registers (table words and everything derived from them) alive across the transform.
-            const uint32_t *tabi = kStream ? table + (int64_t)lvl * tl.words : tab_fixed;
-            asm volatile("" : "+s"(tabi));
+            const uint32_t *tabl = kStream ? table + (int64_t)lvl * tl.words : tab_fixed;
+            asm volatile("" : "+s"(tabl));
+            // (the laundered pointer would be a generic one: loads through it would count as LDS operations too)
+            const GlobalWords tabi = (GlobalWords)tabl;
             const int NG = kStream ? (int)tabi[0] : NG_fixed;
 #pragma unroll
             for (int q = 0; q < P::R; ++q) gw[q] = tabi[tl.gather + lg + P::G * q];
@@ -519,8 +589,11 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
             if ((T & 1) && pair0 + P::FPW >= pairs) {
                 // odd number of increments, last pair: its second step does not exist; what the producer left in
                 // its place (the increment across the sequence boundary) is cleared so that it cannot touch the result
+                // (each wavefront of the transform in the 128-coordinate parts that it has loaded itself: the
+                // others' loads may still be in flight)
                 float2 *st = wave_lds + (int)(pairs - 1 - pair0) * PS;
-                for (int a = sub * 64 + lane; a < twoF; a += 64 * P::WPL) st[a].y = 0.f;
+                for (int j = sub; j < nload; j += P::WPL)
+                    for (int a = 128 * j + lane; a < 128 * j + 128 && a < twoF; a += 64) st[a].y = 0.f;
             }
             transform_fence<P>();
             // 1b. fold the third and later coordinates of a bucket into its first one, one rank per round
@@ -599,13 +672,7 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
             constexpr bool FULL = decltype(full_tag)::value != 0;      // every item of the iteration has both steps
             const int f = tid_here + NT * b;                            // a bin that exists (the caller checks)
             const bool pk = PK && b == 0 && f == 0;
-            auto mul = [&](float2 x, float2 y) { return PK ? cmulf_pk(x, y, pk) : cmulf(x, y); };
-            auto fma = [&](float2 x, float2 y, float2 w) { return PK ? cfmaf_pk(x, y, w, pk) : cfmaf(x, y, w); };
             const bool second_step = FULL || 2 * (pair0_j + s) + 1 < T;    // wavefront-uniform
-            if constexpr (LL == 0) {
-                c.reset();
-                if (pk) c.p0.y = c.p1.y = 1.f;                          // A_0 = 1 in both bins of the packed thread
-            }
             float2 z, zc;
             if constexpr (kEarly) {
                 z = zreg[s][b][j][0];
@@ -615,57 +682,7 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
                 z = Z[pad(f)];
                 zc = Z[kPack ? pad(f > 0 ? D - f : D / 2) : pad((D - f) & (D - 1))];
             }
-            // separation of the two real transforms; for the packed thread z = Z[0], zc = Z[D/2] and
-            // C = (2 Re z, 2 Re zc), (2 Im z, 2 Im zc): the values the general formulas give at f = 0 and f = D/2
-            float2 C0 = make_float2(z.x + zc.x, z.y - zc.y);
-            // a second step that does not exist (odd number of increments) must contribute
-            // exactly nothing; the separation alone would leave rounding noise of the first
-            float2 C1 = make_float2(z.y + zc.y, zc.x - z.x);
-            if constexpr (PK) {
-                if (pk) {
-                    C0 = make_float2(z.x + z.x, zc.x + zc.x);
-                    C1 = make_float2(z.y + z.y, zc.y + zc.y);
-                }
-            }
-            if (!second_step) C1 = make_float2(0.f, 0.f);
-            const float2 a_old = A[b][LL];
-            float2 a_mid = fma(c.p0, C0, a_old);
-            // order >= 2 (a time step may be used up to `order` times in a row, q equal indices weighted
-            // 1/q!): also the values of levels l-2 (and l-3) before each step and the transforms of
-            // levels l-1 (and l-2) at both steps
-            float2 h0 = make_float2(0.f, 0.f), h1 = h0;
-            if constexpr (ORDER >= 2 && LL > 0) {
-                h0 = mul(c.c0p, C0);
-                a_mid = fma(make_float2(0.5f * c.q0.x, 0.5f * c.q0.y), h0, a_mid);
-            }
-            if constexpr (ORDER >= 3 && LL > 1) {
-                const float2 g = mul(c.c0pp, h0);
-                a_mid = fma(make_float2(c.r0.x * (1.0f / 6.0f), c.r0.y * (1.0f / 6.0f)), g, a_mid);
-            }
-            float2 a_new = fma(c.p1, C1, a_mid);
-            if constexpr (ORDER >= 2 && LL > 0) {
-                h1 = mul(c.c1p, C1);
-                a_new = fma(make_float2(0.5f * c.q1.x, 0.5f * c.q1.y), h1, a_new);
-            }
-            if constexpr (ORDER >= 3 && LL > 1) {
-                const float2 g = mul(c.c1pp, h1);
-                a_new = fma(make_float2(c.r1.x * (1.0f / 6.0f), c.r1.y * (1.0f / 6.0f)), g, a_new);
-            }
-            if constexpr (ORDER >= 3) {
-                c.r0 = c.q0;
-                c.r1 = c.q1;
-                c.c0pp = c.c0p;
-                c.c1pp = c.c1p;
-            }
-            if constexpr (ORDER >= 2) {
-                c.q0 = c.p0;
-                c.q1 = c.p1;
-                c.c0p = C0;
-                c.c1p = C1;
-            }
-            A[b][LL] = a_new;
-            c.p0 = a_old;
-            c.p1 = a_mid;
+            level_step<ORDER, LL, PK>(z, zc, pk, second_step, A[b][LL], c);
         };
         // The whole of phase 3, compiled four times: for the wavefront of the packed thread and for the others,
         // and for iterations whose items all exist and have both time steps (all but the last one or two of a

@@ -73,6 +73,7 @@ def test_small_64_rows(oracle):
     (2, 11, 4, 2, 300, 2048),   # D = 2048: one transform per pair of wavefronts
     (1, 6, 2, 8, 16, 2048),     # D = 2048 with eight levels: 1024 threads, 155 KB of LDS
     (2, 5, 3, 5, 1100, 2048),   # D = 2048 with more coordinates than buckets: several staging batches per wavefront
+    (3, 8, 3, 3, 700, 600),     # 600 buckets in a transform of 2048 (two wavefronts per transform), odd number of increments
     (2, 40, 3, 8, 20, 256),     # eight levels
     (2, 30, 3, 9, 12, 64),      # nine levels: generic kernel
     (3, 50, 5, 7, 33, 128),     # seven levels, D = 128
