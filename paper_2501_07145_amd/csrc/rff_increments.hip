@@ -4,6 +4,16 @@
 #include "rfsf_internal.h"
 #include "sincos.h"
 
+// The increments are written once and read once, by the next kernel, long after they have left the caches:
+// non-temporal stores (measured: the projection kernel of Large 8.2 -> 6.4 ms, Long 3 % faster, Medium unchanged;
+// on Small, which would fit the last-level cache, the producer loses what the consumer gains).
+typedef float rfsf_float2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store_stream(float *p, float a, float b)
+{
+    rfsf_float2v v = {a, b};
+    __builtin_nontemporal_store(v, reinterpret_cast<rfsf_float2v *>(p));
+}
+
 namespace rfsf {
 namespace {
 
@@ -116,8 +126,8 @@ __device__ __forceinline__ void sincos_difference_store_pairs(
             const int64_t k0 = k_tile + 8 * q + 4 * half + 2 * j;  // lane-uniform per half-wavefront
             if (f_ok && k0 >= k_lo && k0 <= k_hi) {
                 const uint32_t off = lane_off + (uint32_t)(4 * q + j) * (uint32_t)pair_floats;
-                *reinterpret_cast<float2 *>(cos_base + off) = make_float2(dc[2 * j], dc[2 * j + 1]);
-                *reinterpret_cast<float2 *>(sin_base + off) = make_float2(ds[2 * j], ds[2 * j + 1]);
+                store_stream(cos_base + off, dc[2 * j], dc[2 * j + 1]);
+                store_stream(sin_base + off, ds[2 * j], ds[2 * j + 1]);
             }
         }
     }
