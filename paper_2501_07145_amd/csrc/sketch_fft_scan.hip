@@ -9,6 +9,7 @@
 // FFT (real parts = step k, imaginary parts = step k+1) and are separated again per bin.
 #include "rfsf_internal.h"
 #include "sketch_fft_scan_tuned.h"
+#include "sketch_fft_scan_wide.h"
 #include "sketch_fft_scan_dispatch.h"
 
 namespace rfsf {
@@ -161,8 +162,8 @@ __global__ __launch_bounds__(256) void sketch_fft_scan_generic(
 constexpr int kTableThreads = 1024;
 
 __global__ __launch_bounds__(1024) void build_tables_kernel(
-    const int32_t *__restrict__ hash, const float *__restrict__ sign, int twoF, int D, int Dout, int G,
-    int PD, uint32_t *__restrict__ table)
+    const int32_t *__restrict__ hash, const float *__restrict__ sign, int twoF, int D, int Dout, int G, uint32_t coord_base,
+    uint32_t zero_off, uint32_t *__restrict__ table)
 {
     extern __shared__ __attribute__((aligned(16))) int table_scratch[];
     const int tf4 = (twoF + 3) & ~3;              // keeps the arrays 16-byte aligned
@@ -172,7 +173,6 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(
     const tuned::TableLayout tl = tuned::table_layout(D, G, twoF);
     uint32_t *tab = table + (int64_t)m * tl.words;
     (void)sign;                           // applied by the producing kernel
-    const uint32_t zero_off = (uint32_t)tuned::zero_slot(PD, twoF) * 8u;
 
     for (int a = tid; a < twoF; a += kTableThreads) h[a] = ((hash[(int64_t)m * twoF + a] % Dout) + Dout) % Dout;
     for (int e = tid; e < D; e += kTableThreads) { src0[e] = -1; src1[e] = -1; }
@@ -206,8 +206,8 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(
     __syncthreads();
     for (int i = tid; i < n_rounds * G; i += kTableThreads) tab[tl.fold + i] = zero_off | (tuned::kFoldPad << 16);
     for (int e = tid; e < D; e += kTableThreads) {
-        const uint32_t s0 = src0[e] >= 0 ? (uint32_t)src0[e] * 8u : zero_off;
-        const uint32_t s1 = src1[e] >= 0 ? (uint32_t)src1[e] * 8u : zero_off;
+        const uint32_t s0 = src0[e] >= 0 ? coord_base + (uint32_t)src0[e] * 8u : zero_off;
+        const uint32_t s1 = src1[e] >= 0 ? coord_base + (uint32_t)src1[e] * 8u : zero_off;
         tab[tl.gather + e] = s0 | (s1 << 16);
     }
     __syncthreads();                      // padding entries are in place before the real ones land
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(1024) void build_tables_kernel(
             idx += (u.x == r) + (u.y == r) + (u.z == r) + (u.w == r) + (w.x == r) + (w.y == r) + (w.z == r) + (w.w == r);
         }
         for (; a2 < a; ++a2) idx += rk[a2] == r;
-        tab[tl.fold + cls[r] + idx] = ((uint32_t)a * 8u) | (((uint32_t)src0[h[a]] * 8u) << 16);
+        tab[tl.fold + cls[r] + idx] = (coord_base + (uint32_t)a * 8u) | ((coord_base + (uint32_t)src0[h[a]] * 8u) << 16);
     }
 }
 
@@ -257,8 +257,15 @@ size_t sketch_fft_scan_state_bytes(int64_t n_seq, int M, int D, int order)
 
 namespace {
 struct TunedGeometry { int G /* entries per fold round */, PD, FPW, NTWL; };
+// transforms of 4096 and 8192: the kernel of sketch_fft_scan_wide.h
+bool wide_shape(int D) { return D == 4096 || D == 8192; }
+size_t table_builder_lds(int twoF, int D) { return sizeof(int) * (size_t)(3 * ((twoF + 3) & ~3) + 4 + 2 * D); }
 bool tuned_geometry(int D, TunedGeometry *g)
 {
+    if (wide_shape(D)) {
+        *g = {64, 0, 1, tuned::Plan<10>::NTWL};
+        return true;
+    }
     switch (D) {
 #define RFSF_GEOM(L2) case 1 << L2: *g = {tuned::Plan<L2>::GF, tuned::Plan<L2>::PD, tuned::Plan<L2>::FPW, tuned::Plan<L2>::NTWL}; return true;
         RFSF_GEOM(6) RFSF_GEOM(7) RFSF_GEOM(8) RFSF_GEOM(9) RFSF_GEOM(10) RFSF_GEOM(11)
@@ -272,6 +279,7 @@ size_t sketch_fft_scan_lds_bytes(int M, int F, int D)
 {
     TunedGeometry g;
     if (!tuned_geometry(D, &g)) return 0;
+    if (wide_shape(D)) return tuned::wide_lds_bytes(D / 1024, M, F);
     int log2d = 0;
     while ((1 << log2d) < D) ++log2d;
     return sizeof(float2) * ((size_t)tuned::transforms_in_flight(M, log2d) * g.FPW * tuned::slot_stride(g.PD, 2 * F) + g.NTWL);
@@ -283,6 +291,7 @@ bool sketch_fft_scan_is_tuned(int M, int F, int D)
     // F <= 4032: the staging area (2F rounded up to 128 coordinates) and the zero float2 behind it are
     // addressed with 16-bit byte offsets
     if (M > 8 || F > 4032 || !tuned_geometry(D, &g)) return false;
+    if (wide_shape(D) && table_builder_lds(2 * F, D) > kLdsPerCu) return false;
     return sketch_fft_scan_lds_bytes(M, F, D) <= kLdsPerCu;
 }
 
@@ -304,7 +313,7 @@ hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int
     TunedGeometry g;
     if (!sketch_fft_scan_is_tuned(M, F, D) || !tuned_geometry(D, &g)) return hipSuccess;   // generic kernel: no table
     const int twoF = 2 * F;
-    const size_t lds = sizeof(int) * (size_t)(3 * ((twoF + 3) & ~3) + 4 + 2 * D);
+    const size_t lds = table_builder_lds(twoF, D);
     if (lds > 64 * 1024) {
         static size_t granted = 0;
         if (lds > granted) {
@@ -314,8 +323,11 @@ hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int
             granted = lds;
         }
     }
+    // byte offsets within a slot: of coordinate 0 and of the float2 that is always zero
+    const uint32_t coord_base = wide_shape(D) ? 8u * tuned::kWideStageBase : 0u;
+    const uint32_t zero_off = wide_shape(D) ? 0u : 8u * (uint32_t)tuned::zero_slot(g.PD, twoF);
     hipLaunchKernelGGL(build_tables_kernel, dim3((unsigned)M), dim3(kTableThreads), lds, stream, hash, sign, twoF, D, Dout,
-                       g.G, g.PD, table);
+                       g.G, coord_base, zero_off, table);
     return hipGetLastError();
 }
 
@@ -334,6 +346,8 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
             case 8: return tuned::dispatch_levels_8(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
             case 9: return tuned::dispatch_levels_9(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
             case 10: return tuned::dispatch_levels_10(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            case 12: return tuned::dispatch_levels_12(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            case 13: return tuned::dispatch_levels_13(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
             default: return tuned::dispatch_levels_11(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
         }
     }

@@ -17,6 +17,8 @@ RFSF_DECLARE_DISPATCH(8)
 RFSF_DECLARE_DISPATCH(9)
 RFSF_DECLARE_DISPATCH(10)
 RFSF_DECLARE_DISPATCH(11)
+RFSF_DECLARE_DISPATCH(12)
+RFSF_DECLARE_DISPATCH(13)
 #undef RFSF_DECLARE_DISPATCH
 
 }  // namespace tuned
