@@ -309,6 +309,39 @@ def test_signature_order_three(oracle, N, L, d, M, F, D):
         assert e.value.code == -9
 
 
+@pytest.mark.parametrize("N,L,d,M,F,D,order", [
+    (2, 9, 3, 1, 40, 4096, 1),       # one level: a single level slot per workgroup
+    (2, 8, 3, 2, 40, 4096, 2),       # two levels: level l belongs to slot l for good; odd number of increments
+    (3, 12, 3, 3, 700, 4096, 1),     # three levels dealt to two slots; 1400 coordinates
+    (2, 7, 2, 5, 64, 4096, 3),       # five levels, order 3
+    (2, 6, 2, 8, 24, 4096, 1),       # eight levels
+    (2, 5, 3, 2, 3000, 4096, 1),     # more coordinates than buckets: the staging area exceeds the transform
+    (2, 9, 3, 2, 40, 4000, 1),       # 8192 points, two levels (4000 buckets)
+    (2, 8, 3, 2, 300, 3000, 2),      # 8192 points, two levels, order 2
+    (3, 11, 3, 5, 500, 1000, 1),     # the paper's largest projection size at its truncation level
+    (2, 6, 2, 5, 500, 1000, 3),      # ... with order 3, odd number of increments
+    (2, 10, 2, 8, 100, 1000, 1),     # eight levels of 1000 buckets
+    (3, 13, 4, 5, 250, 500, 2),      # 500 buckets at five levels: 4096 points
+])
+def test_transforms_of_4096_and_8192(oracle, N, L, d, M, F, D, order):
+    """Bucket counts whose transform has 4096 or 8192 points (4096 itself and non-powers of two, convolved linearly
+    and folded at the end): several interleaved 1024-point transforms and a combining pass, levels dealt to two
+    level slots. Also as a batch of different lengths."""
+    inp = _random_case(900 + D + L + M, N, L, d, M, F, D)
+    got = _gpu_features(inp, D, order=order).cpu().numpy()
+    want = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D, order=order)
+    err = block_errors(got, want, M, D)
+    print(f"D={D} M={M} F={F} L={L} order {order}: block errors", err)
+    assert np.all(err <= FP32_BLOCK_TOL)
+    lengths = np.array(([L, 1, max(1, L - 1)])[:N])
+    t = _dev(inp)
+    got_r = rfsf.rfsf_ts_features(t["X"], t["W"], t["hash"], t["sign"], inp["lengthscale"], D, order=order,
+                                  lengths=torch.from_numpy(lengths).cuda()).cpu().numpy()
+    want_r = oracle.features_ragged(inp["X"], lengths, inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D,
+                                    order=order)
+    assert np.all(block_errors(got_r, want_r, M, D) <= FP32_BLOCK_TOL)
+
+
 @pytest.mark.parametrize("L", [2, 3, 4, 5, 6, 7, 10, 17])
 @pytest.mark.parametrize("M,order", [(5, 1), (6, 1), (5, 2), (6, 3)])
 def test_levels_dealt_to_eight_wavefronts(oracle, L, M, order):
