@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "librfsf_ts.so")
 SOURCES = ["rfsf_ts_api.hip", "rff_increments.hip", "sketch_fft_scan.hip", "gram.hip", "normalize.hip", "dp1d.hip", "trp.hip"] + \
-    [f"sketch_fft_scan_d{n}.hip" for n in range(6, 14)]
+    [f"sketch_fft_scan_d{n}.hip" for n in list(range(6, 14)) + [100, 200, 500, 1000]]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

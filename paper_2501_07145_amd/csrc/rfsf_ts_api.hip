@@ -43,14 +43,16 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 bool is_pow2_in_range(int32_t D) { return D >= 2 && D <= 4096 && (D & (D - 1)) == 0; }
 
 // Length of the FFTs. A power-of-two bucket count is transformed as it is (circular convolution
-// modulo D). Any other D >= 1 takes the next power of two that holds the linear convolution of M
-// sketches of length D without wrap-around, M*(D-1)+1 numbers; the kernels fold the result modulo D
-// at the end. 0 if that exceeds the largest transform (8192, which covers the paper's own largest
-// projection size, 1000, at its truncation level 5).
-int transform_length(int32_t M, int32_t D)
+// modulo D), and so are the bucket counts 100, 200, 500 and 1000 of the paper's own experiments, which have
+// transforms of their own (radices 10, 5, 2), as long as the shape fits the tuned kernel. Any other D >= 1
+// takes the next power of two that holds the linear convolution of M sketches of length D without
+// wrap-around, M*(D-1)+1 numbers; the kernels fold the result modulo D at the end. 0 if that exceeds the
+// largest transform (8192).
+int transform_length(int32_t M, int32_t F, int32_t D)
 {
     if (is_pow2_in_range(D)) return D;
     if (D < 1 || D > 4096) return 0;
+    if ((D == 100 || D == 200 || D == 500 || D == 1000) && rfsf::sketch_fft_scan_is_tuned(M, F, D)) return D;
     const int64_t need = (int64_t)M * (D - 1) + 1;
     int64_t P = 2;
     while (P < need) P *= 2;
@@ -64,7 +66,7 @@ int check_shape(const rfsf_ts_shape *s)
     if (s->N > ((int64_t)1 << 40) || s->L > ((int64_t)1 << 40) || s->d > (1 << 20) || s->M > (1 << 10) ||
         s->F > (1 << 24))
         return RFSF_E_BAD_SHAPE;
-    if (transform_length(s->M, s->D) == 0) return RFSF_E_D_NOT_POW2;
+    if (transform_length(s->M, s->F, s->D) == 0) return RFSF_E_D_NOT_POW2;
     if (s->order < 0) return RFSF_E_BAD_SHAPE;
     if (s->ld_out < 1 + (int64_t)s->M * s->D) return RFSF_E_BAD_STRIDE;
     return RFSF_OK;
@@ -75,13 +77,13 @@ void per_sequence_bytes(const rfsf_ts_shape *s, size_t *incr, size_t *state)
 {
     // rows of increments per sequence: L in the row layout, L rounded up to even in the pair layout
     *incr = (size_t)((s->L + 1) & ~(int64_t)1) * (size_t)s->M * 2u * (size_t)s->F * sizeof(float);
-    *state = rfsf::sketch_fft_scan_state_bytes(1, s->M, transform_length(s->M, s->D), s->order == 2 ? 2 : 1);
+    *state = rfsf::sketch_fft_scan_state_bytes(1, s->M, transform_length(s->M, s->F, s->D), s->order == 2 ? 2 : 1);
 }
 
 // Fixed part: packed hash/sign table plus room for aligning the three sections.
 size_t fixed_bytes(const rfsf_ts_shape *s)
 {
-    return align_up(rfsf::sketch_fft_scan_table_bytes(s->M, s->F, transform_length(s->M, s->D))) + kIncrementTail +
+    return align_up(rfsf::sketch_fft_scan_table_bytes(s->M, s->F, transform_length(s->M, s->F, s->D))) + kIncrementTail +
            3 * kAlign;
 }
 
@@ -190,7 +192,7 @@ int features_impl(const rfsf_ts_shape *shape, const float *X, const int64_t *len
     if (shape->rff_bf16 != 0 && shape->d > 128) return RFSF_E_UNSUPPORTED;
     if (shape->order > 3) return RFSF_E_UNSUPPORTED;
     if ((int64_t)shape->M * 2 * shape->F > ((int64_t)1 << 26)) return RFSF_E_UNSUPPORTED;   // 32-bit row offsets
-    if (!rfsf::sketch_fft_scan_fits(shape->M, shape->F, transform_length(shape->M, shape->D), shape->order < 2 ? 1 : shape->order))
+    if (!rfsf::sketch_fft_scan_fits(shape->M, shape->F, transform_length(shape->M, shape->F, shape->D), shape->order < 2 ? 1 : shape->order))
         return RFSF_E_UNSUPPORTED;        // order 3 outside the tuned kernel's shapes
     if (!workspace) return RFSF_E_NULLPTR;
     int64_t chunk = chunk_for(shape, workspace_bytes);
@@ -202,7 +204,7 @@ int features_impl(const rfsf_ts_shape *shape, const float *X, const int64_t *len
     char *base = static_cast<char *>(workspace);
     const size_t mis = (size_t)(reinterpret_cast<uintptr_t>(base) % kAlign);
     char *p_table = base + (mis ? kAlign - mis : 0);
-    const int P = transform_length(shape->M, shape->D);
+    const int P = transform_length(shape->M, shape->F, shape->D);
     char *p_incr = p_table + align_up(rfsf::sketch_fft_scan_table_bytes(shape->M, shape->F, P));
     char *p_state = p_incr + align_up((size_t)chunk * incr + kIncrementTail);
     float *dphi = reinterpret_cast<float *>(p_incr);

@@ -270,6 +270,9 @@ bool tuned_geometry(int D, TunedGeometry *g)
 #define RFSF_GEOM(L2) case 1 << L2: *g = {tuned::Plan<L2>::GF, tuned::Plan<L2>::PD, tuned::Plan<L2>::FPW, tuned::Plan<L2>::NTWL}; return true;
         RFSF_GEOM(6) RFSF_GEOM(7) RFSF_GEOM(8) RFSF_GEOM(9) RFSF_GEOM(10) RFSF_GEOM(11)
 #undef RFSF_GEOM
+#define RFSF_GEOM(DD) case DD: *g = {tuned::Plan<DD>::GF, tuned::Plan<DD>::PD, tuned::Plan<DD>::FPW, tuned::Plan<DD>::NTWL}; return true;
+        RFSF_GEOM(100) RFSF_GEOM(200) RFSF_GEOM(500) RFSF_GEOM(1000)        // exact transforms, 2^a 5^b points
+#undef RFSF_GEOM
         default: return false;
     }
 }
@@ -280,8 +283,9 @@ size_t sketch_fft_scan_lds_bytes(int M, int F, int D)
     TunedGeometry g;
     if (!tuned_geometry(D, &g)) return 0;
     if (wide_shape(D)) return tuned::wide_lds_bytes(D / 1024, M, F);
-    int log2d = 0;
+    int log2d = 0;                        // the key of the kernel's plan: log2 D, or D itself for the exact lengths
     while ((1 << log2d) < D) ++log2d;
+    if ((1 << log2d) != D) log2d = D;
     return sizeof(float2) * ((size_t)tuned::transforms_in_flight(M, log2d) * g.FPW * tuned::slot_stride(g.PD, 2 * F) + g.NTWL);
 }
 
@@ -340,6 +344,13 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
     int log2D = 0;
     while ((1 << log2D) < D) ++log2D;
     if (sketch_fft_scan_is_tuned(M, F, D)) {
+        switch (D) {
+            case 100: return tuned::dispatch_levels_100(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            case 200: return tuned::dispatch_levels_200(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            case 500: return tuned::dispatch_levels_500(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            case 1000: return tuned::dispatch_levels_1000(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            default: break;
+        }
         switch (log2D) {
             case 6: return tuned::dispatch_levels_6(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
             case 7: return tuned::dispatch_levels_7(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);

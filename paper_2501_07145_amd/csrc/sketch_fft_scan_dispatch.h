@@ -19,6 +19,10 @@ RFSF_DECLARE_DISPATCH(10)
 RFSF_DECLARE_DISPATCH(11)
 RFSF_DECLARE_DISPATCH(12)
 RFSF_DECLARE_DISPATCH(13)
+RFSF_DECLARE_DISPATCH(100)
+RFSF_DECLARE_DISPATCH(200)
+RFSF_DECLARE_DISPATCH(500)
+RFSF_DECLARE_DISPATCH(1000)
 #undef RFSF_DECLARE_DISPATCH
 
 }  // namespace tuned

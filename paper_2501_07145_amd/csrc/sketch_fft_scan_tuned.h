@@ -90,8 +90,46 @@ struct Plan {
     static constexpr int wb_off(int p) { return p == 0 ? 0 : wb_off(p - 1) + R / radix(p - 1); }
     static constexpr int NTW = tw_off(NP) == 0 ? 1 : tw_off(NP);
     static constexpr int NWB = wb_off(NP);
-    static constexpr int roff(int q) { return G >= 16 ? q * (G + G / 16) : pad(G * q); }
+    static constexpr int roff(int q) { return G >= 16 ? q * (G + G / 16) : tuned::pad(G * q); }
+    static constexpr int pad(int e) { return tuned::pad(e); }     // position in a slot of element e
 };
+
+// Transform lengths 2^a 5^b that the paper's own experiments use as bucket counts (100, 200, 500, 1000): exact
+// transforms of that length instead of a linear convolution in the next power of two above M (D - 1) + 1.
+// 20 points per lane, D / 20 lanes per transform (the remaining lanes of a wavefront repeat the work of the
+// first ones, see the kernel), passes of radix 10, 10 and 10 / 5 / 2 / none; slots are not padded; the
+// twiddles of all passes after the first live in the LDS table. Selected as Plan<D>.
+template <int DD>
+struct MixedPlan {
+    static constexpr int LOG2D = DD;
+    static constexpr int D = DD;
+    static constexpr int R = 20;
+    static constexpr int G = D / R;
+    static constexpr int WPL = 1;
+    static constexpr int FPW = 64 / G;
+    static constexpr int GF = G;
+    static constexpr int PD = D;
+    static constexpr int NP = D == 100 ? 2 : 3;
+    static constexpr int radix(int p) { return p < 2 ? 10 : (D == 1000 ? 10 : (D == 500 ? 5 : 2)); }
+    static constexpr int Ns(int p) { return p == 0 ? 1 : Ns(p - 1) * radix(p - 1); }
+    static constexpr int tw_sets(int p) { return G % Ns(p) == 0 ? 1 : R / radix(p); }
+    static constexpr bool tw_in_lds(int p) { return p > 0; }
+    static constexpr int tw_regs(int) { return 0; }
+    static constexpr int tw_lds(int p) { return tw_in_lds(p) ? tw_sets(p) * (radix(p) - 1) * G : 0; }
+    static constexpr int tw_off(int) { return 0; }
+    static constexpr int twl_off(int p) { return p <= 1 ? 0 : twl_off(p - 1) + tw_lds(p - 1); }
+    static constexpr int NTWL = twl_off(NP);
+    static constexpr int wb_off(int p) { return p == 0 ? 0 : wb_off(p - 1) + R / radix(p - 1); }
+    static constexpr int NTW = 1;
+    static constexpr int NWB = wb_off(NP);
+    static constexpr int roff(int q) { return G * q; }
+    static constexpr int pad(int e) { return e; }
+    static_assert(D % R == 0 && G * FPW <= 64, "");
+};
+template <> struct Plan<100> : MixedPlan<100> {};
+template <> struct Plan<200> : MixedPlan<200> {};
+template <> struct Plan<500> : MixedPlan<500> {};
+template <> struct Plan<1000> : MixedPlan<1000> {};
 
 // Geometry of one LDS slot (float2 units): [0, ZS) data -- the staging area uses [0, 2F) and, because a
 // direct load always deposits 128 coordinates, junk up to the next multiple of 128; the transform uses
@@ -176,6 +214,58 @@ __device__ __forceinline__ float2 cfmaf(float2 a, float2 b, float2 c)   // a * b
     return make_float2(fmaf(a.x, b.x, fmaf(-a.y, b.y, c.x)), fmaf(a.x, b.y, fmaf(a.y, b.x, c.y)));
 }
 
+// In-register forward DFT of 5 points at x[B], x[B + ST], ..., natural order in and out.
+template <int B, int ST, int TOTAL>
+__device__ __forceinline__ void dft5(float2 (&x)[TOTAL])
+{
+    constexpr float c1 = 0.30901699437494742f, c2 = -0.80901699437494742f;    // cos(2 pi / 5), cos(4 pi / 5)
+    constexpr float s1 = 0.95105651629515357f, s2 = 0.58778525229247313f;     // sin(2 pi / 5), sin(4 pi / 5)
+    const float2 x0 = x[B], x1 = x[B + ST], x2 = x[B + 2 * ST], x3 = x[B + 3 * ST], x4 = x[B + 4 * ST];
+    const float2 t1 = make_float2(x1.x + x4.x, x1.y + x4.y), t2 = make_float2(x2.x + x3.x, x2.y + x3.y);
+    const float2 t3 = make_float2(x1.x - x4.x, x1.y - x4.y), t4 = make_float2(x2.x - x3.x, x2.y - x3.y);
+    x[B] = make_float2(x0.x + t1.x + t2.x, x0.y + t1.y + t2.y);
+    const float2 a1 = make_float2(fmaf(c1, t1.x, fmaf(c2, t2.x, x0.x)), fmaf(c1, t1.y, fmaf(c2, t2.y, x0.y)));
+    const float2 a2 = make_float2(fmaf(c2, t1.x, fmaf(c1, t2.x, x0.x)), fmaf(c2, t1.y, fmaf(c1, t2.y, x0.y)));
+    const float2 b1 = make_float2(fmaf(s1, t3.x, s2 * t4.x), fmaf(s1, t3.y, s2 * t4.y));
+    const float2 b2 = make_float2(fmaf(s2, t3.x, -s1 * t4.x), fmaf(s2, t3.y, -s1 * t4.y));
+    // X1 = a1 - i b1, X4 = a1 + i b1, X2 = a2 - i b2, X3 = a2 + i b2
+    x[B + ST] = make_float2(a1.x + b1.y, a1.y - b1.x);
+    x[B + 4 * ST] = make_float2(a1.x - b1.y, a1.y + b1.x);
+    x[B + 2 * ST] = make_float2(a2.x + b2.y, a2.y - b2.x);
+    x[B + 3 * ST] = make_float2(a2.x - b2.y, a2.y + b2.x);
+}
+
+// In-register forward DFT of 10 points, natural order in and out: one radix-2 stage (decimation in frequency),
+// then the even outputs are the 5-point transform of the sums and the odd ones that of the twiddled differences.
+__device__ __forceinline__ void dft10(float2 (&x)[10])
+{
+    constexpr float wc[5] = {1.0f, 0.80901699437494742f, 0.30901699437494742f, -0.30901699437494742f, -0.80901699437494742f};
+    constexpr float ws[5] = {0.0f, 0.58778525229247313f, 0.95105651629515357f, 0.95105651629515357f, 0.58778525229247313f};
+    float2 y[10];                                            // y[2 t] sums, y[2 t + 1] differences times exp(-2 pi i t / 10)
+#pragma unroll
+    for (int t = 0; t < 5; ++t) {
+        const float2 a = x[t], b = x[t + 5];
+        y[2 * t] = make_float2(a.x + b.x, a.y + b.y);
+        const float dx = a.x - b.x, dy = a.y - b.y;
+        y[2 * t + 1] = t == 0 ? make_float2(dx, dy) : make_float2(fmaf(dx, wc[t], dy * ws[t]), fmaf(dy, wc[t], -dx * ws[t]));
+    }
+    dft5<0, 2, 10>(y);                                       // y[2 k]     = X[2 k]
+    dft5<1, 2, 10>(y);                                       // y[2 k + 1] = X[2 k + 1]
+#pragma unroll
+    for (int k = 0; k < 10; ++k) x[k] = y[k];
+}
+
+// Forward DFT of r points in registers; output k is left at position dft_out<r>(k).
+template <int r>
+__device__ __forceinline__ void dft_small(float2 (&x)[r])
+{
+    if constexpr (r == 10) dft10(x);
+    else if constexpr (r == 5) dft5<0, 1, 5>(x);
+    else dft_dif<r, 0, r>(x);
+}
+template <int r>
+constexpr int dft_out(int k) { return (r & (r - 1)) == 0 ? bitrev(k, ilog2(r)) : k; }
+
 // The same for a thread whose float2 are not complex numbers but two independent reals (pk; bins 0 and D/2
 // of a real sequence's transform, which one thread carries in the two halves of its values): the products
 // become componentwise. With pk false these are cmulf and cfmaf, operation for operation.
@@ -219,7 +309,7 @@ struct WaveFft {
 
     __device__ __forceinline__ void init(int lg, float2 *twl_table)
     {
-        rbase = pad(lg);
+        rbase = P::pad(lg);
         twl = twl_table + lg;
         init_pass<0>(lg);
         fill_table<1>(twl_table);
@@ -234,7 +324,7 @@ struct WaveFft {
                 constexpr int r = P::radix(PI), Ns = P::Ns(PI);
                 for (int i = threadIdx.x; i < P::tw_lds(PI); i += blockDim.x) {
                     const int l = i % P::G, ut = i / P::G, t = ut % (r - 1) + 1, u = ut / (r - 1);
-                    const int k = (l + P::G * u) & (Ns - 1);
+                    const int k = (l + P::G * u) % Ns;
                     float s, c;
                     sincospif(-2.0f * (float)(k * t) / (float)(Ns * r), &s, &c);
                     twl_table[P::twl_off(PI) + i] = make_float2(c, s);
@@ -252,14 +342,14 @@ struct WaveFft {
 #pragma unroll
             for (int u = 0; u < NB; ++u) {
                 const int j = lg + P::G * u;
-                const int k = j & (Ns - 1);
-                wbase[P::wb_off(PI) + u] = pad((j - k) * r + k);
+                const int k = j % Ns;
+                wbase[P::wb_off(PI) + u] = P::pad((j - k) * r + k);
             }
             if constexpr (PI > 0 && !P::tw_in_lds(PI)) {
                 constexpr int NSETS = P::tw_sets(PI);
 #pragma unroll
                 for (int u = 0; u < NSETS; ++u) {
-                    const int k = (lg + P::G * u) & (Ns - 1);
+                    const int k = (lg + P::G * u) % Ns;
 #pragma unroll
                     for (int t = 1; t < r; ++t) {
                         float s, c;
@@ -290,7 +380,7 @@ struct WaveFft {
     __device__ __forceinline__ void run_pass(float2 *slot, float2 (&v)[P::R]) const
     {
         if constexpr (PI < P::NP) {
-            constexpr int r = P::radix(PI), Ns = P::Ns(PI), NB = P::R / r, LR = ilog2(r);
+            constexpr int r = P::radix(PI), Ns = P::Ns(PI), NB = P::R / r;
             transform_fence<P>();                    // every lane has its inputs in registers
 #pragma unroll
             for (int u = 0; u < NB; ++u) {
@@ -310,10 +400,10 @@ struct WaveFft {
                         }
                     }
                 }
-                dft_dif<r, 0, r>(x);
+                dft_small<r>(x);
                 float2 *dst = slot + wbase[P::wb_off(PI) + u];
 #pragma unroll
-                for (int t = 0; t < r; ++t) dst[pad(t * Ns)] = x[bitrev(t, LR)];
+                for (int t = 0; t < r; ++t) dst[P::pad(t * Ns)] = x[dft_out<r>(t)];
             }
             transform_fence<P>();
             if constexpr (PI + 1 < P::NP) {
@@ -334,7 +424,7 @@ struct WaveFft {
 // that take the (pair, level) transforms of the sequence in order, 8 at a time, whatever level they belong to.
 // (Measured against one wavefront per level at 100 steps: D = 1024 +10 % with 5 levels, +23 % with 6, -9 % with
 // 7; D = 512 +-1 %; D <= 256, where a wavefront carries four or more transforms, 35-60 % slower.)
-__host__ __device__ constexpr int transforms_in_flight(int M, int LOG2D) { return (LOG2D == 10 && (M == 5 || M == 6)) ? 8 : M; }
+__host__ __device__ constexpr int transforms_in_flight(int M, int LOG2D) { return ((LOG2D == 10 || LOG2D == 1000) && (M == 5 || M == 6)) ? 8 : M; }
 
 typedef const __attribute__((address_space(1))) uint32_t *GlobalWords;   // table words, known to be in global memory
 
@@ -481,8 +571,12 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
     extern __shared__ float2 lds[];                    // [NTR][FPW][PS] slots, then the twiddle table
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wv = wave / P::WPL, sub = wave % P::WPL;       // transform of the workgroup, wavefront within it
-    const int slot_id = P::WPL > 1 ? 0 : lane / P::G;
-    const int lg = P::WPL > 1 ? sub * 64 + lane : lane % P::G; // lane within the transform
+    // lanes beyond the G * FPW that the wavefront's transforms occupy (lengths that are no power of two) repeat the
+    // work of the first ones: same addresses, same values
+    constexpr int kLanesUsed = P::WPL > 1 ? 64 : P::G * P::FPW;
+    const int lane_t = kLanesUsed < 64 && lane >= kLanesUsed ? lane - kLanesUsed : lane;
+    const int slot_id = P::WPL > 1 ? 0 : lane_t / P::G;
+    const int lg = P::WPL > 1 ? sub * 64 + lane : lane_t % P::G; // lane within the transform
     const int twoF = 2 * F;
     const int ZS = zero_slot(P::PD, twoF), PS = slot_stride(P::PD, twoF);
     float2 *twl_table = lds + (size_t)NTR * P::FPW * PS;        // behind the slots
@@ -641,7 +735,7 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
         // whole iteration as loop invariants, where they were spilled to scratch (measured: 8 % faster
         // there, slower for the other transform lengths).
         int tid_here = tid;
-        if constexpr (LOG2D == 10) asm volatile("" : "+v"(tid_here));
+        if constexpr (LOG2D == 10 || LOG2D == 1000) asm volatile("" : "+v"(tid_here));
         float2 zreg[kEarly ? P::FPW : 1][kEarly ? BPT : 1][kEarly ? NTR : 1][2];
         if constexpr (kEarly) {
 #pragma unroll
@@ -649,8 +743,8 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
 #pragma unroll
                 for (int b = 0; b < BPT; ++b) {
                     const int f = tid_here + NT * b;
-                    const int fi = pad(f < NB ? f : 0);
-                    const int fc = kPack ? pad(f > 0 && f < NB ? D - f : D / 2) : pad((D - (f < NB ? f : 0)) & (D - 1));
+                    const int fi = P::pad(f < NB ? f : 0);
+                    const int fc = kPack ? P::pad(f > 0 && f < NB ? D - f : D / 2) : P::pad(f > 0 && f < NB ? D - f : 0);
 #pragma unroll
                     for (int j = 0; j < NTR; ++j) {
                         const float2 *Z = lds + ((size_t)j * P::FPW + s) * PS;
@@ -679,8 +773,8 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
                 zc = zreg[s][b][j][1];
             } else {
                 const float2 *Z = lds + ((size_t)j * P::FPW + s) * PS;
-                z = Z[pad(f)];
-                zc = Z[kPack ? pad(f > 0 ? D - f : D / 2) : pad((D - f) & (D - 1))];
+                z = Z[P::pad(f)];
+                zc = Z[kPack ? P::pad(f > 0 ? D - f : D / 2) : P::pad(f > 0 ? D - f : 0)];
             }
             level_step<ORDER, LL, PK>(z, zc, pk, second_step, A[b][LL], c);
         };
@@ -749,11 +843,11 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
                 float2 *Y = lds + (size_t)l * P::FPW * PS;
                 const float2 y = A[b][l];
                 if (kPack && f == 0) {                       // bins 0 and D/2, both real
-                    Y[pad(0)] = make_float2(y.x, 0.f);
-                    Y[pad(D / 2)] = make_float2(y.y, 0.f);
+                    Y[P::pad(0)] = make_float2(y.x, 0.f);
+                    Y[P::pad(D / 2)] = make_float2(y.y, 0.f);
                 } else {
-                    Y[pad(f)] = make_float2(y.x, -y.y);
-                    if (f > 0 && f < D / 2) Y[pad(D - f)] = y;
+                    Y[P::pad(f)] = make_float2(y.x, -y.y);
+                    if (f > 0 && f < D / 2) Y[P::pad(D - f)] = y;
                 }
             }
         }
@@ -770,7 +864,7 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
         // and the linear result is folded modulo Dout here.
         for (int j = sub * 64 + lane; j < Dout; j += 64 * P::WPL) {
             float acc = 0.f;
-            for (int e = j; e < D; e += Dout) acc += wave_lds[pad(e)].x;
+            for (int e = j; e < D; e += Dout) acc += wave_lds[P::pad(e)].x;
             row[1 + (int64_t)wv * Dout + j] = acc * invD;
         }
     }
