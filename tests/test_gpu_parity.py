@@ -309,6 +309,42 @@ def test_signature_order_three(oracle, N, L, d, M, F, D):
         assert e.value.code == -9
 
 
+@pytest.mark.parametrize("D", [100, 200, 500, 1000])
+@pytest.mark.parametrize("M,F,L,order", [
+    (1, 30, 9, 1),        # one level
+    (2, 64, 8, 2),        # order 2, odd number of increments
+    (3, 130, 12, 3),      # order 3
+    (4, 50, 31, 1),       # several iterations, F < D/2 for the larger D
+    (5, 700, 6, 1),       # more coordinates than buckets for most D; five levels (D = 1000: dealt to eight wavefronts)
+    (6, 33, 14, 2),       # six levels
+    (8, 20, 7, 1),        # eight levels
+])
+def test_bucket_counts_of_the_papers_experiments(oracle, D, M, F, L, order):
+    """D = 100, 200, 500, 1000 (Sec. 4 of the paper uses such projection sizes) have transforms of exactly that
+    length: radix-10, -5 and -2 passes, lanes beyond D/20 per transform repeating the first ones. Also as a batch
+    of different lengths, and with nine levels, where the shape leaves the tuned kernel and takes the
+    linear-convolution route again."""
+    N, d = 3, 3
+    inp = _random_case(1000 + D + L + M, N, L, d, M, F, D)
+    got = _gpu_features(inp, D, order=order).cpu().numpy()
+    want = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D, order=order)
+    err = block_errors(got, want, M, D)
+    print(f"D={D} M={M} F={F} L={L} order {order}: block errors", err)
+    assert np.all(err <= FP32_BLOCK_TOL)
+    lengths = np.array([L, 1, max(1, L - 1)])
+    t = _dev(inp)
+    got_r = rfsf.rfsf_ts_features(t["X"], t["W"], t["hash"], t["sign"], inp["lengthscale"], D, order=order,
+                                  lengths=torch.from_numpy(lengths).cuda()).cpu().numpy()
+    want_r = oracle.features_ragged(inp["X"], lengths, inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D,
+                                    order=order)
+    assert np.all(block_errors(got_r, want_r, M, D) <= FP32_BLOCK_TOL)
+
+
+def test_nine_levels_of_a_hundred_buckets_take_the_linear_route(oracle):
+    inp = _random_case(77, 2, 6, 2, 9, 12, 100)
+    _check(inp, 100, oracle)
+
+
 @pytest.mark.parametrize("N,L,d,M,F,D,order", [
     (2, 9, 3, 1, 40, 4096, 1),       # one level: a single level slot per workgroup
     (2, 8, 3, 2, 40, 4096, 2),       # two levels: level l belongs to slot l for good; odd number of increments
