@@ -7,9 +7,11 @@
  *   N  sequences                      L  time points per sequence, T = L-1 increments
  *   d  state dimension                M  truncation level
  *   F  random Fourier frequencies per level [paper: D]; the static features have 2F dims
- *   D  count-sketch buckets per level [paper: Q]; a power of two in [2, 4096] is fastest; any other
- *      D is accepted as long as M*(D-1)+1 <= 8192 (the convolutions are then evaluated as linear
- *      ones with a longer power-of-two transform and folded modulo D at the end)
+ *   D  count-sketch buckets per level [paper: Q]; powers of two in [2, 4096] and the values 100,
+ *      200, 500, 1000 (the projection sizes of the paper's experiments, Sec. 4) have transforms of
+ *      exactly that length and are fastest; any other D is accepted as long as M*(D-1)+1 <= 8192
+ *      (the convolutions are then evaluated as linear ones with a longer power-of-two transform and
+ *      folded modulo D at the end)
  *
  * General rules for every entry point
  *   - Every data pointer is a DEVICE pointer on the current HIP device, owned by
