@@ -129,6 +129,31 @@ def test_full_size(oracle, name, n_oracle, n_identity):
         assert gram_error(Ksub, oracle.gram(want)) <= (5 * GRAM_TOL if w.rff_bf16 else GRAM_TOL)
 
 
+@pytest.mark.parametrize("D,F,N", [(1000, 500, 3000), (500, 250, 4000), (3000, 256, 600)])
+def test_projection_sizes_that_are_no_power_of_two(oracle, D, F, N):
+    """Five levels with the paper's largest projection size (1000: exact transform, items dealt to eight
+    wavefronts), with 500, and with 3000 buckets (linear route in 8192 points: wide kernel) at batch sizes that
+    fill the chip several times: oracle on sampled rows, bucket-sum identity on more."""
+    import dataclasses
+    w = dataclasses.replace(wl.WORKLOADS["medium"], N=N, L=60, d=6, M=5 if D < 3000 else 2, F=F, D=D)
+    tables = wl.make_tables(w, 3)
+    X = wl.make_paths(w, 3)
+    rec, _ = rfsf.rfsf_ts_workspace_bytes(w.N, w.L, w.d, w.M, w.F, w.D, w.rff_bf16)
+    workspace = torch.empty(rec, dtype=torch.uint8, device="cuda")
+    out = _features(w, X, tables, workspace)
+    ls = float(np.float32(w.lengthscale))
+    rng = np.random.default_rng(6)
+    sel = np.unique(np.concatenate([[0, w.N - 1], rng.integers(0, w.N, size=6)]))
+    got = out[torch.from_numpy(sel).cuda()].cpu().numpy()
+    want = oracle.features(X[sel], tables[0], tables[1], tables[2], ls, w.D)
+    err = block_errors(got, want, w.M, w.D)
+    print(f"D={D}: {len(sel)} oracle rows, block errors {err}")
+    assert np.all(err <= FP32_BLOCK_TOL)
+    rows = rng.integers(0, w.N, size=256)
+    worst = _bucket_sum_identity(w, X[rows], tables[0], tables[2], out[torch.from_numpy(rows).cuda()].cpu().numpy(), 2e-5)
+    print(f"D={D}: bucket-sum identity on 256 rows, worst relative deviation {worst:.2e}")
+
+
 def test_hundred_thousand_time_points(oracle):
     """The paper's scalability claim for the primal methods is sequence length 1e5 and beyond (Sec. 4).
     Two sequences of 100001 points in the paper's own shape (d = 5, M = 5, feature and projection size
