@@ -405,7 +405,7 @@ def main() -> int:
                     help="medium (default) is the largest configuration that runs in fp32 throughout")
     ap.add_argument("--also", default=None,
                     help="comma-separated further workloads measured after the headline one with their own default "
-                         "step counts and reported under 'other_workloads' (default: small,long,large when the "
+                         "step counts and reported under 'other_workloads' (default: small,long,large,paper when the "
                          "headline is the default medium run, none otherwise; 'none' switches it off)")
     ap.add_argument("--cpu-rows", type=int, default=-1, help="oracle sample size (-1: per-workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -424,7 +424,7 @@ def main() -> int:
     default_run = args.workload == "medium" and args.variant == "ts" and not args.normalize and \
         args.workspace_mib == 0 and args.copy_probe_mib == 0
     if args.also is None:
-        args.also = "small,long,large" if default_run else "none"
+        args.also = "small,long,large,paper" if default_run else "none"
     if args.steps is None:
         args.steps = DEFAULT_STEPS[args.workload][0]
     if args.warmup is None:

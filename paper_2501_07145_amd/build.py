@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "librfsf_ts.so")
 SOURCES = ["rfsf_ts_api.hip", "rff_increments.hip", "sketch_fft_scan.hip", "gram.hip", "normalize.hip", "dp1d.hip", "trp.hip"] + \
-    [f"sketch_fft_scan_d{n}.hip" for n in list(range(6, 14)) + [100, 200, 500, 1000]]
+    [f"sketch_fft_scan_d{n}.hip" for n in [6, 7, 8, 9, 10, 12, 13, 100, 200, 500, 1000, 2048]]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

@@ -268,10 +268,11 @@ bool tuned_geometry(int D, TunedGeometry *g)
     }
     switch (D) {
 #define RFSF_GEOM(L2) case 1 << L2: *g = {tuned::Plan<L2>::GF, tuned::Plan<L2>::PD, tuned::Plan<L2>::FPW, tuned::Plan<L2>::NTWL}; return true;
-        RFSF_GEOM(6) RFSF_GEOM(7) RFSF_GEOM(8) RFSF_GEOM(9) RFSF_GEOM(10) RFSF_GEOM(11)
+        RFSF_GEOM(6) RFSF_GEOM(7) RFSF_GEOM(8) RFSF_GEOM(9) RFSF_GEOM(10)
 #undef RFSF_GEOM
 #define RFSF_GEOM(DD) case DD: *g = {tuned::Plan<DD>::GF, tuned::Plan<DD>::PD, tuned::Plan<DD>::FPW, tuned::Plan<DD>::NTWL}; return true;
         RFSF_GEOM(100) RFSF_GEOM(200) RFSF_GEOM(500) RFSF_GEOM(1000)        // exact transforms, 2^a 5^b points
+        RFSF_GEOM(2048)                                                     // 32 points per lane
 #undef RFSF_GEOM
         default: return false;
     }
@@ -285,7 +286,7 @@ size_t sketch_fft_scan_lds_bytes(int M, int F, int D)
     if (wide_shape(D)) return tuned::wide_lds_bytes(D / 1024, M, F);
     int log2d = 0;                        // the key of the kernel's plan: log2 D, or D itself for the exact lengths
     while ((1 << log2d) < D) ++log2d;
-    if ((1 << log2d) != D) log2d = D;
+    if ((1 << log2d) != D || D == 2048) log2d = D;       // (2048 has a plan of its own kind, too)
     return sizeof(float2) * ((size_t)tuned::transforms_in_flight(M, log2d) * g.FPW * tuned::slot_stride(g.PD, 2 * F) + g.NTWL);
 }
 
@@ -349,6 +350,7 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
             case 200: return tuned::dispatch_levels_200(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
             case 500: return tuned::dispatch_levels_500(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
             case 1000: return tuned::dispatch_levels_1000(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            case 2048: return tuned::dispatch_levels_2048(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
             default: break;
         }
         switch (log2D) {
@@ -359,7 +361,7 @@ hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const 
             case 10: return tuned::dispatch_levels_10(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
             case 12: return tuned::dispatch_levels_12(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
             case 13: return tuned::dispatch_levels_13(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
-            default: return tuned::dispatch_levels_11(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            default: return hipErrorInvalidValue;
         }
     }
     if (order > 2) return hipErrorInvalidValue;           // order 3 exists in the tuned kernel only

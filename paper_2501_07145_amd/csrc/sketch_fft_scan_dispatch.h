@@ -16,13 +16,13 @@ RFSF_DECLARE_DISPATCH(7)
 RFSF_DECLARE_DISPATCH(8)
 RFSF_DECLARE_DISPATCH(9)
 RFSF_DECLARE_DISPATCH(10)
-RFSF_DECLARE_DISPATCH(11)
 RFSF_DECLARE_DISPATCH(12)
 RFSF_DECLARE_DISPATCH(13)
 RFSF_DECLARE_DISPATCH(100)
 RFSF_DECLARE_DISPATCH(200)
 RFSF_DECLARE_DISPATCH(500)
 RFSF_DECLARE_DISPATCH(1000)
+RFSF_DECLARE_DISPATCH(2048)
 #undef RFSF_DECLARE_DISPATCH
 
 }  // namespace tuned

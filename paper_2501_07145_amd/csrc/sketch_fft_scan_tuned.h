@@ -1,8 +1,8 @@
 // Tuned kernel for steps 3-4 (CountSketch, Fourier-domain level recursion over time, inverse
 // transform; Sec. 3.5, eqs. (cs), (ts_def), (ts_rec) with p = 1).
 //
-// Work decomposition (one workgroup per sequence, M wavefronts, wavefront m owns level m; for D = 2048
-// two wavefronts share a level and its single transform, see Plan::WPL):
+// Work decomposition (one workgroup per sequence, M wavefronts, wavefront m owns level m; a transform always
+// lives in one wavefront: 16 points per lane up to D = 1024, 32 for D = 2048):
 //   per iteration every wavefront handles FPW pairs of consecutive time steps of its level:
 //     1. CountSketch as a gather. The signed increments of the 2*FPW time steps arrive in LDS in
 //        their natural order (step 2k -> real part, step 2k+1 -> imaginary part of the float2 of
@@ -44,16 +44,17 @@ namespace tuned {
 // Stockham passes and the contiguous accesses are both free of bank conflicts.
 __host__ __device__ constexpr int pad(int e) { return e + (e >> 4); }
 
-template <int LOG2D_>
+template <int LOG2D_, int LOG2R_ = 4>
 struct Plan {
     static constexpr int LOG2D = LOG2D_;
     static constexpr int D = 1 << LOG2D;
-    static constexpr int LOG2R = 4;
+    static constexpr int LOG2R = LOG2R_;
+    static constexpr int kMinWaves = LOG2R_ > 4 ? 2 : 4;   // wavefronts per SIMD the register budget is set for
     static constexpr int R = 1 << LOG2R;        // points per lane
-    static constexpr int G = D / R;             // lanes per transform (128 for D = 2048: two wavefronts)
-    static constexpr int WPL = G > 64 ? G / 64 : 1;   // wavefronts per level
-    static constexpr int FPW = G > 64 ? 1 : 64 / G;   // transforms per wavefront (per level when WPL > 1)
-    static constexpr int GF = G > 64 ? 64 : G;  // entries per fold round (the first wavefront of a level folds)
+    static constexpr int G = D / R;             // lanes per transform
+    static_assert(G <= 64, "a transform lives in one wavefront");
+    static constexpr int FPW = 64 / G;          // transforms per wavefront
+    static constexpr int GF = G;                // entries per fold round
     static constexpr int PD = D + D / 16;       // padded transform length in float2
     static constexpr int NP = LOG2D <= 4 ? 1 : (LOG2D <= 8 ? 2 : 3);
     static constexpr int radix(int p)
@@ -71,7 +72,7 @@ struct Plan {
             // half the registers and half the LDS per workgroup doubles the resident workgroups, which
             // outweighs the extra LDS exchange (measured: 20 % faster)
             case 10: return p == 1 ? 4 : 16;
-            default: return p == 1 ? 8 : 16;    // 11: 16 points per lane, two wavefronts per transform
+            default: return p == 1 ? 8 : 16;    // 11 (32 points per lane)
         }
     }
     static constexpr int Ns(int p) { return p == 0 ? 1 : Ns(p - 1) * radix(p - 1); }
@@ -105,7 +106,6 @@ struct MixedPlan {
     static constexpr int D = DD;
     static constexpr int R = 20;
     static constexpr int G = D / R;
-    static constexpr int WPL = 1;
     static constexpr int FPW = 64 / G;
     static constexpr int GF = G;
     static constexpr int PD = D;
@@ -124,12 +124,16 @@ struct MixedPlan {
     static constexpr int NWB = wb_off(NP);
     static constexpr int roff(int q) { return G * q; }
     static constexpr int pad(int e) { return e; }
+    static constexpr int kMinWaves = 4;
     static_assert(D % R == 0 && G * FPW <= 64, "");
 };
 template <> struct Plan<100> : MixedPlan<100> {};
 template <> struct Plan<200> : MixedPlan<200> {};
 template <> struct Plan<500> : MixedPlan<500> {};
 template <> struct Plan<1000> : MixedPlan<1000> {};
+// 2048 points in one wavefront: 32 points per lane (twice the registers, half the resident wavefronts, no barrier
+// inside the transform). Selected as Plan<2048>.
+template <> struct Plan<2048> : Plan<11, 5> {};
 
 // Geometry of one LDS slot (float2 units): [0, ZS) data -- the staging area uses [0, 2F) and, because a
 // direct load always deposits 128 coordinates, junk up to the next multiple of 128; the transform uses
@@ -289,14 +293,11 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Exchange point inside a transform: a compiler-level ordering when the transform lives in one
-// wavefront, a workgroup barrier when it spans several (every wavefront of the workgroup runs the same
-// sequence of passes, so the barriers match up).
+// Exchange point inside a transform, which lives in one wavefront: a compiler-level ordering.
 template <typename P>
 __device__ __forceinline__ void transform_fence()
 {
-    if constexpr (P::WPL > 1) __syncthreads();
-    else wave_lds_fence();
+    wave_lds_fence();
 }
 
 // Per-lane constants of the wavefront-local FFT.
@@ -424,7 +425,7 @@ struct WaveFft {
 // that take the (pair, level) transforms of the sequence in order, 8 at a time, whatever level they belong to.
 // (Measured against one wavefront per level at 100 steps: D = 1024 +10 % with 5 levels, +23 % with 6, -9 % with
 // 7; D = 512 +-1 %; D <= 256, where a wavefront carries four or more transforms, 35-60 % slower.)
-__host__ __device__ constexpr int transforms_in_flight(int M, int LOG2D) { return ((LOG2D == 10 || LOG2D == 1000) && (M == 5 || M == 6)) ? 8 : M; }
+__host__ __device__ constexpr int transforms_in_flight(int M, int LOG2D) { return ((LOG2D == 10 || LOG2D == 1000) && (M == 5 || M == 6)) || (LOG2D == 2048 && M >= 3 && M <= 7) ? 8 : M; }
 
 typedef const __attribute__((address_space(1))) uint32_t *GlobalWords;   // table words, known to be in global memory
 
@@ -547,8 +548,8 @@ __device__ __forceinline__ void level_step(float2 z, float2 zc, bool pk, bool se
 }
 
 template <int LOG2D, int M, int ORDER, int NTR>
-__global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
-    __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::WPL == 1 ? 4 : 3, 4))) void sketch_fft_scan_kernel(
+__global__ __launch_bounds__(64 * NTR)
+    __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::kMinWaves, 4))) void sketch_fft_scan_kernel(
     const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L,
     const int64_t *__restrict__ lengths, int F, int Dout, float *__restrict__ out, int64_t ld_out)
 {
@@ -557,11 +558,11 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
     // sequence in that order, so a wavefront changes level from iteration to iteration and an iteration
     // may end in the middle of a pair; otherwise transform w of the workgroup is always level w.
     constexpr bool kStream = NTR != M;
-    static_assert(!kStream || (P::WPL == 1 && NTR > M), "streaming needs one wavefront per transform and a slot per level");
+    static_assert(!kStream || NTR > M, "streaming needs a slot per level");
     // Bins of phase 3: f = 0 .. D/2, thread t owning f = t, t + NT, ... The transforms of real sequences are real
     // at f = 0 and f = D/2. Where that saves a bin per thread (NT divides D/2), thread 0 carries both in one
     // float2 (bin 0 in .x, bin D/2 in .y; kPack) and the bins are f = 0 .. D/2 - 1.
-    constexpr int D = P::D, NT = 64 * NTR * P::WPL;
+    constexpr int D = P::D, NT = 64 * NTR;
     constexpr bool kPack = (D / 2) % NT == 0;
     constexpr int NB = kPack ? D / 2 : D / 2 + 1, BPT = (NB + NT - 1) / NT;
     // Phase 3 is compiled separately for iterations in which every item exists and has both time steps (no
@@ -570,13 +571,13 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
     constexpr bool kSplitFull = P::FPW <= 2;
     extern __shared__ float2 lds[];                    // [NTR][FPW][PS] slots, then the twiddle table
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wv = wave / P::WPL, sub = wave % P::WPL;       // transform of the workgroup, wavefront within it
+    const int wv = wave;                                     // transform of the workgroup
     // lanes beyond the G * FPW that the wavefront's transforms occupy (lengths that are no power of two) repeat the
     // work of the first ones: same addresses, same values
-    constexpr int kLanesUsed = P::WPL > 1 ? 64 : P::G * P::FPW;
+    constexpr int kLanesUsed = P::G * P::FPW;
     const int lane_t = kLanesUsed < 64 && lane >= kLanesUsed ? lane - kLanesUsed : lane;
-    const int slot_id = P::WPL > 1 ? 0 : lane_t / P::G;
-    const int lg = P::WPL > 1 ? sub * 64 + lane : lane_t % P::G; // lane within the transform
+    const int slot_id = lane_t / P::G;
+    const int lg = lane_t % P::G;                            // lane within the transform
     const int twoF = 2 * F;
     const int ZS = zero_slot(P::PD, twoF), PS = slot_stride(P::PD, twoF);
     float2 *twl_table = lds + (size_t)NTR * P::FPW * PS;        // behind the slots
@@ -612,8 +613,7 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
         for (int l = 0; l < M; ++l) A[b][l] = make_float2(0.f, 0.f);
 
     // Staging: pair pair0 + s of level lvl goes to slot s of the wavefront, 128 coordinates (1 KB) per
-    // instruction, lane i supplying coordinates 2i and 2i+1. The wavefronts of a transform take the
-    // instructions in turn. Pairs beyond the last one (final group only) are redirected to the last pair and
+    // instruction, lane i supplying coordinates 2i and 2i+1. Pairs beyond the last one (final group only) are redirected to the last pair and
     // ignored later; coordinates beyond 2F read the following floats of the workspace (which is padded at its
     // end for this) and land in the unused part of the staging area.
     auto stage_direct = [&](int lvl, int64_t pair0) {
@@ -622,7 +622,7 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
             const int64_t p = pair0 + s < pairs ? pair0 + s : pairs - 1;
             const float *src = (kStream ? seq + (int64_t)lvl * 2 * twoF : seq_fixed) + p * pf + 4 * lane;
             float2 *dst = wave_lds + s * PS;
-            for (int j = sub; j < nload; j += P::WPL)
+            for (int j = 0; j < nload; ++j)
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + 256 * j),
                                                  (__attribute__((address_space(3))) void *)(dst + 128 * j), 16, 0, 0);
         }
@@ -634,7 +634,7 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
     // (Measured: 3-4 % on D = 1024 and 2048 with five levels; with 32 float2 -- D = 512, four levels -- it no
     // longer pays, and loading the next iteration's table words early as well costs more registers than it hides.)
     constexpr int ZREGS = P::FPW * BPT * NTR * 2;
-    constexpr bool kEarly = ZREGS <= 24;
+    constexpr bool kEarly = ZREGS <= (P::kMinWaves <= 2 ? 64 : 24);    // (a plan with twice the registers per wavefront affords more)
     uint32_t gw[P::R], fw[kFoldInRegs];
 
     // The item of this wavefront: level and first pair of its transform in the current iteration (a transform
@@ -683,15 +683,11 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
             if ((T & 1) && pair0 + P::FPW >= pairs) {
                 // odd number of increments, last pair: its second step does not exist; what the producer left in
                 // its place (the increment across the sequence boundary) is cleared so that it cannot touch the result
-                // (each wavefront of the transform in the 128-coordinate parts that it has loaded itself: the
-                // others' loads may still be in flight)
                 float2 *st = wave_lds + (int)(pairs - 1 - pair0) * PS;
-                for (int j = sub; j < nload; j += P::WPL)
-                    for (int a = 128 * j + lane; a < 128 * j + 128 && a < twoF; a += 64) st[a].y = 0.f;
+                for (int a = lane; a < twoF; a += 64) st[a].y = 0.f;
             }
             transform_fence<P>();
             // 1b. fold the third and later coordinates of a bucket into its first one, one rank per round
-            // (by the first wavefront of the transform when it spans several)
             auto fold = [&](uint32_t w) {
                 const uint32_t own = w & 0xffffu, tgt = w >> 16;
                 if (tgt != kFoldPad) {
@@ -701,13 +697,10 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
                 }
                 wave_lds_fence();
             };
-            if (sub == 0) {
 #pragma unroll
-                for (int g = 0; g < kFoldInRegs; ++g)
-                    if (g < NG) fold(fw[g]);
-                for (int g = kFoldInRegs; g < NG; ++g) fold(tabi[tl.fold + g * P::GF + (lg % P::GF)]);
-            }
-            if constexpr (P::WPL > 1) __syncthreads();
+            for (int g = 0; g < kFoldInRegs; ++g)
+                if (g < NG) fold(fw[g]);
+            for (int g = kFoldInRegs; g < NG; ++g) fold(tabi[tl.fold + g * P::GF + (lg % P::GF)]);
             // 1c. gather: first and second coordinate of each of this lane's buckets
             float2 v[P::R];
 #pragma unroll
@@ -862,7 +855,7 @@ __global__ __launch_bounds__(64 * NTR * Plan<LOG2D>::WPL)
         // Dout buckets per level. Dout == D: the transform was circular in D already. Dout < D (a bucket
         // count that is no power of two): D was chosen so large that the M-fold convolution never wrapped,
         // and the linear result is folded modulo Dout here.
-        for (int j = sub * 64 + lane; j < Dout; j += 64 * P::WPL) {
+        for (int j = lane; j < Dout; j += 64) {
             float acc = 0.f;
             for (int e = j; e < D; e += Dout) acc += wave_lds[P::pad(e)].x;
             row[1 + (int64_t)wv * Dout + j] = acc * invD;
