@@ -423,9 +423,12 @@ struct WaveFft {
 // workgroup, 15.6 wavefronts for 4 or 8 per workgroup: the dispatcher reserves registers for
 // ceil(wavefronts / 4) wavefronts on every SIMD). For D = 1024 those level counts therefore run 8 wavefronts
 // that take the (pair, level) transforms of the sequence in order, 8 at a time, whatever level they belong to.
-// (Measured against one wavefront per level at 100 steps: D = 1024 +10 % with 5 levels, +23 % with 6, -9 % with
-// 7; D = 512 +-1 %; D <= 256, where a wavefront carries four or more transforms, 35-60 % slower.)
-__host__ __device__ constexpr int transforms_in_flight(int M, int LOG2D) { return ((LOG2D == 10 || LOG2D == 1000) && (M == 5 || M == 6)) || (LOG2D == 2048 && M >= 3 && M <= 7) ? 8 : M; }
+// (Measured against one wavefront per level at 100 steps: D = 1024 +10 % with 5 levels, +23 % with 6, -9 to -15 %
+// with 7; D = 512 +-1 %; D <= 256, where a wavefront carries four or more transforms, 35-60 % slower.) The
+// same helps where one wavefront per level gives a CU too few wavefronts for other reasons: D = 1024 and 1000
+// with up to three levels (+3-7 %; four levels: +-1 %), and D = 2048, whose slots let one workgroup per CU
+// be resident whatever its size (up to seven levels: +10-20 %, one level +15 %, two +-0).
+__host__ __device__ constexpr int transforms_in_flight(int M, int LOG2D) { return ((LOG2D == 10 || LOG2D == 1000) && (M <= 3 || M == 5 || M == 6)) || (LOG2D == 2048 && M <= 7) ? 8 : M; }
 
 typedef const __attribute__((address_space(1))) uint32_t *GlobalWords;   // table words, known to be in global memory
 
