@@ -799,7 +799,10 @@ __global__ __launch_bounds__(64 * NTR)
                     });
                 });
             } else {
-#pragma unroll
+                // with more than four transforms per wavefront and three or more levels the loop over the pairs
+                // stays a loop: unrolled it needs 50-150 spilled registers (measured rolled: D = 64 ... 200 with
+                // 4-8 levels 1.4-3 times faster; with one or two levels up to 45 % slower, hence the condition)
+#pragma unroll(P::FPW > 4 && M >= 3 ? 1 : P::FPW)
                 for (int s = 0; s < P::FPW; ++s) {
                     if (!FULL && pair0_now + s >= pairs) continue;             // slot without a pair (last iteration only)
 #pragma unroll
