@@ -550,9 +550,19 @@ __device__ __forceinline__ void level_step(float2 z, float2 zc, bool pk, bool se
     c.p1 = a_mid;
 }
 
+// Wavefronts per SIMD the register budget of the kernel is set for: the plan's, except that workgroups of 5 or 6
+// wavefronts with 6 to 12 transforms per wavefront (D = 100, 128, 200) get 96 registers: their workgroups then
+// find room on a CU more often (see transforms_in_flight; measured +8-15 %).
+template <int LOG2D, int M>
+constexpr int kernel_min_waves()
+{
+    using P = Plan<LOG2D>;
+    return (P::FPW > 4 && P::FPW < 16 && (M == 5 || M == 6)) ? 5 : P::kMinWaves;
+}
+
 template <int LOG2D, int M, int ORDER, int NTR>
 __global__ __launch_bounds__(64 * NTR)
-    __attribute__((amdgpu_waves_per_eu(Plan<LOG2D>::kMinWaves, 4))) void sketch_fft_scan_kernel(
+    __attribute__((amdgpu_waves_per_eu(kernel_min_waves<LOG2D, M>(), kernel_min_waves<LOG2D, M>() > 4 ? 8 : 4))) void sketch_fft_scan_kernel(
     const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L,
     const int64_t *__restrict__ lengths, int F, int Dout, float *__restrict__ out, int64_t ld_out)
 {
