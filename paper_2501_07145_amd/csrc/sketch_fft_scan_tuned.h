@@ -427,8 +427,13 @@ struct WaveFft {
 // with 7; D = 512 +-1 %; D <= 256, where a wavefront carries four or more transforms, 35-60 % slower.) The
 // same helps where one wavefront per level gives a CU too few wavefronts for other reasons: D = 1024 and 1000
 // with up to three levels (+3-7 %; four levels: +-1 %), and D = 2048, whose slots let one workgroup per CU
-// be resident whatever its size (up to seven levels: +10-20 %, one level +15 %, two +-0).
-__host__ __device__ constexpr int transforms_in_flight(int M, int LOG2D) { return ((LOG2D == 10 || LOG2D == 1000) && (M <= 3 || M == 5 || M == 6)) || (LOG2D == 2048 && M <= 7) ? 8 : M; }
+// be resident whatever its size (up to seven levels: +10-20 %, one level +15 %, two +-0). D = 500 with 5 or 6
+// levels gains 16 %, D = 512 with 5 levels 3 % (with 6: none); D = 256 loses 40 %.
+__host__ __device__ constexpr int transforms_in_flight(int M, int LOG2D) {
+    return ((LOG2D == 10 || LOG2D == 1000) && (M <= 3 || M == 5 || M == 6)) || (LOG2D == 2048 && M <= 7) ||
+                   (LOG2D == 500 && (M == 5 || M == 6)) || (LOG2D == 9 && M == 5)
+               ? 8 : M;
+}
 
 typedef const __attribute__((address_space(1))) uint32_t *GlobalWords;   // table words, known to be in global memory
 

@@ -309,6 +309,26 @@ def test_signature_order_three(oracle, N, L, d, M, F, D):
         assert e.value.code == -9
 
 
+@pytest.mark.parametrize("L", [2, 3, 5, 8, 13, 21, 34])
+@pytest.mark.parametrize("order", [1, 2, 3])
+def test_two_pairs_per_wavefront_dealt_to_eight_wavefronts(oracle, L, order):
+    """Transforms of 512 with five levels: the items, here groups of two pairs of one level, go to eight
+    wavefronts in order; the lengths give last groups with one and with two pairs and last iterations with
+    different numbers of items. Also as a batch of different lengths."""
+    N, d, M, F, D = 4, 3, 5, 40, 512
+    inp = _random_case(1200 + L, N, L, d, M, F, D)
+    got = _gpu_features(inp, D, order=order).cpu().numpy()
+    want = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D, order=order)
+    assert np.all(block_errors(got, want, M, D) <= FP32_BLOCK_TOL)
+    lengths = np.array([L, 1, max(1, L - 1), max(1, L // 2)])
+    t = _dev(inp)
+    got_r = rfsf.rfsf_ts_features(t["X"], t["W"], t["hash"], t["sign"], inp["lengthscale"], D, order=order,
+                                  lengths=torch.from_numpy(lengths).cuda()).cpu().numpy()
+    want_r = oracle.features_ragged(inp["X"], lengths, inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D,
+                                    order=order)
+    assert np.all(block_errors(got_r, want_r, M, D) <= FP32_BLOCK_TOL)
+
+
 @pytest.mark.parametrize("D", [100, 200, 500, 1000])
 @pytest.mark.parametrize("M,F,L,order", [
     (1, 30, 9, 1),        # one level
