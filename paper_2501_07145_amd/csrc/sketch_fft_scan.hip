@@ -243,7 +243,7 @@ __global__ void validate_tables_kernel(const int32_t *hash, const float *sign, i
 }  // namespace
 
 namespace {
-constexpr size_t kLdsPerCu = 160 * 1024;
+using tuned::kLdsPerCu;
 size_t generic_lds_bytes(int D, int order) { return sizeof(float2) * (size_t)generic_buffer_elems(D, order); }
 bool generic_in_global(int D, int order) { return generic_lds_bytes(D, order) > kLdsPerCu; }
 }  // namespace
@@ -287,7 +287,9 @@ size_t sketch_fft_scan_lds_bytes(int M, int F, int D)
     int log2d = 0;                        // the key of the kernel's plan: log2 D, or D itself for the exact lengths
     while ((1 << log2d) < D) ++log2d;
     if ((1 << log2d) != D || D == 2048) log2d = D;       // (2048 has a plan of its own kind, too)
-    return sizeof(float2) * ((size_t)tuned::transforms_in_flight(M, log2d) * g.FPW * tuned::slot_stride(g.PD, 2 * F) + g.NTWL);
+    // eight wavefronts taking the items in order where the plan prefers that and the slots fit, else one per level
+    const size_t preferred = tuned::tuned_lds_bytes(tuned::transforms_in_flight(M, log2d), g.FPW, g.PD, g.NTWL, F);
+    return preferred <= kLdsPerCu ? preferred : tuned::tuned_lds_bytes(M, g.FPW, g.PD, g.NTWL, F);
 }
 
 bool sketch_fft_scan_is_tuned(int M, int F, int D)

@@ -437,6 +437,13 @@ __host__ __device__ constexpr int transforms_in_flight(int M, int LOG2D) {
 
 typedef const __attribute__((address_space(1))) uint32_t *GlobalWords;   // table words, known to be in global memory
 
+constexpr size_t kLdsPerCu = 160 * 1024;
+// LDS of a workgroup with NTR transforms in flight: their slots and the twiddle table of the plan.
+__host__ __device__ constexpr size_t tuned_lds_bytes(int NTR, int FPW, int PD, int NTWL, int F)
+{
+    return sizeof(float2) * ((size_t)NTR * FPW * slot_stride(PD, 2 * F) + NTWL);
+}
+
 template <int LL>
 struct LevelTag {
     static constexpr int value = LL;

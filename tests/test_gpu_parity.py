@@ -72,7 +72,8 @@ def test_small_64_rows(oracle):
     (3, 24, 6, 5, 100, 1024),   # D = 1024, three-pass transform
     (2, 11, 4, 2, 300, 2048),   # D = 2048: one transform per pair of wavefronts
     (1, 6, 2, 8, 16, 2048),     # D = 2048 with eight levels: 1024 threads, 155 KB of LDS
-    (2, 5, 3, 5, 1100, 2048),   # D = 2048 with more coordinates than buckets: several staging batches per wavefront
+    (2, 5, 3, 5, 1100, 2048),   # D = 2048 with more coordinates than buckets: eight slots exceed the LDS, one wavefront per level
+    (2, 7, 3, 5, 1500, 1024),   # the same for D = 1024 with five levels
     (3, 8, 3, 3, 700, 600),     # 600 buckets in a transform of 2048 (two wavefronts per transform), odd number of increments
     (2, 40, 3, 8, 20, 256),     # eight levels
     (2, 30, 3, 9, 12, 64),      # nine levels: generic kernel
