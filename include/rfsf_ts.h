@@ -9,9 +9,9 @@
  *   F  random Fourier frequencies per level [paper: D]; the static features have 2F dims
  *   D  count-sketch buckets per level [paper: Q]; powers of two in [2, 4096] and the values 100,
  *      200, 500, 1000 (the projection sizes of the paper's experiments, Sec. 4) have transforms of
- *      exactly that length and are fastest; any other D is accepted as long as M*(D-1)+1 <= 8192
- *      (the convolutions are then evaluated as linear ones with a longer power-of-two transform and
- *      folded modulo D at the end)
+ *      exactly that length and are fastest (D < 64 runs in a transform of 64 points); any other D is
+ *      accepted as long as M*(D-1)+1 <= 8192 (the convolutions are then evaluated as linear ones with
+ *      a longer power-of-two transform and folded modulo D at the end)
  *
  * General rules for every entry point
  *   - Every data pointer is a DEVICE pointer on the current HIP device, owned by

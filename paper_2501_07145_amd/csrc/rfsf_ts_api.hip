@@ -42,21 +42,29 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 bool is_pow2_in_range(int32_t D) { return D >= 2 && D <= 4096 && (D & (D - 1)) == 0; }
 
-// Length of the FFTs. A power-of-two bucket count is transformed as it is (circular convolution
-// modulo D), and so are the bucket counts 100, 200, 500 and 1000 of the paper's own experiments, which have
-// transforms of their own (radices 10, 5, 2), as long as the shape fits the tuned kernel. Any other D >= 1
-// takes the next power of two that holds the linear convolution of M sketches of length D without
-// wrap-around, M*(D-1)+1 numbers; the kernels fold the result modulo D at the end. 0 if that exceeds the
-// largest transform (8192).
+// Length of the FFTs. The convolutions are circular modulo D; a transform of P points gives them exactly when
+// D divides P (the result, circular modulo P, is folded modulo D at the end) or when P holds the linear
+// convolution of M sketches of length D without wrap-around, M*(D-1)+1 numbers. Candidates, in this order: D
+// itself when it is a power of two in [2, 4096] or one of 100, 200, 500, 1000 (the bucket counts of the paper's
+// own experiments, which have transforms of their own with radices 10, 5, 2); then the powers of two from 64 on
+// that are multiples of D or hold the linear convolution. The first one whose shape fits a tuned kernel is
+// taken (a small D with many random features, for instance, does not fit at its own length: its wavefronts
+// would carry 16 staging areas each); if none does, the first candidate at all, for the generic kernel.
+// 0 if there is no candidate up to 8192 points.
 int transform_length(int32_t M, int32_t F, int32_t D)
 {
-    if (is_pow2_in_range(D)) return D;
     if (D < 1 || D > 4096) return 0;
-    if ((D == 100 || D == 200 || D == 500 || D == 1000) && rfsf::sketch_fft_scan_is_tuned(M, F, D)) return D;
+    const bool pow2 = is_pow2_in_range(D);
+    const bool own = pow2 || D == 100 || D == 200 || D == 500 || D == 1000;
+    if (own && rfsf::sketch_fft_scan_is_tuned(M, F, D)) return D;
     const int64_t need = (int64_t)M * (D - 1) + 1;
-    int64_t P = 2;
-    while (P < need) P *= 2;
-    return P <= 8192 ? (int)P : 0;
+    int first = pow2 ? D : 0;
+    for (int64_t P = 2; P <= 8192; P *= 2) {
+        if (!(pow2 ? P >= D : P >= need)) continue;
+        if (first == 0) first = (int)P;
+        if (P >= 64 && rfsf::sketch_fft_scan_is_tuned(M, F, (int)P)) return (int)P;
+    }
+    return first;
 }
 
 int check_shape(const rfsf_ts_shape *s)

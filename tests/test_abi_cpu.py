@@ -96,9 +96,9 @@ def test_bucket_counts_that_are_no_power_of_two_are_accepted_when_small():
 
 
 def test_order_three_outside_the_tuned_shapes_is_refused_before_anything_is_enqueued():
-    # D = 16 and nine levels run the generic kernel, which has orders 1 and 2 only
+    # nine levels run the generic kernel, which has orders 1 and 2 only
     lib = binding.load_library()
-    for D, M in ((16, 2), (64, 9)):
+    for D, M in ((16, 9), (64, 9)):
         shp = _shape(D=D, M=M, ld_out=1 + M * D, order=3)
         assert lib.rfsf_ts_features(ctypes.byref(shp), 256, 256, 256, 256, 1.0, 256, 256, 1 << 30, None) == -9
     # the tuned kernel addresses a slot with 16-bit byte offsets: 4032 random features at most

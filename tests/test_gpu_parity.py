@@ -303,10 +303,14 @@ def test_signature_order_three(oracle, N, L, d, M, F, D):
     two = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D, order=2)
     if M >= 3:
         assert block_errors(got, two, M, D)[2:].max() > 1e-3        # it is not the order-2 map
-    if D == 64:     # outside the tuned kernel's shapes order 3 is refused
+    if D == 64:     # 16 buckets run in a transform of 64 points (tuned kernel: order 3 there too) ...
         small = _random_case(1, 2, 6, 2, 2, 4, 16)
+        got16 = _gpu_features(small, 16, order=3).cpu().numpy()
+        want16 = oracle.features(small["X"], small["W"], small["hash"], small["sign"], small["lengthscale"], 16, order=3)
+        assert np.all(block_errors(got16, want16, 2, 16) <= FP32_BLOCK_TOL)
+        nine = _random_case(2, 2, 6, 2, 9, 4, 16)           # ... nine levels leave the tuned kernels: refused
         with pytest.raises(binding.RfsfTsError) as e:
-            _gpu_features(small, 16, order=3)
+            _gpu_features(nine, 16, order=3)
         assert e.value.code == -9
 
 
