@@ -32,8 +32,9 @@ MFMA_FP32_PEAK_TFLOPS = 157.3    # MI355X dense fp32 matrix, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix, published
 
 
-VALU_FP32_PEAK_TFLOPS = 157.3    # MI355X fp32 vector, published (needs packed fp32; 78.6 without)
-COS_FLOPS = 18                   # range reduction (5) + two degree-3 polynomials in r^2 (13) of the cosine used
+VALU_FP32_UNPACKED_TFLOPS = 78.6  # fp32 vector without packed instructions (157.3 with): one fused multiply-add per lane
+                                  # and cycle on 256 CUs x 64 lanes at 2.4 GHz, the rate this library's code can reach
+COS_FLOPS = 20                   # argument (fma), reduction by pi (fma, sub, 2 fma), r^2, degree-5 polynomial in r^2 (5 fma)
 
 
 def bench_dp1d(args, w, inp, dev, ls) -> int:
@@ -72,16 +73,24 @@ def bench_dp1d(args, w, inp, dev, ls) -> int:
     rfsf.rfsf_ts_profile_enable(False)
 
     units = w.N * w.L
-    flops_per_unit = w.M * w.F * (2.0 * w.d + COS_FLOPS + 4.0)       # projection, cosine, difference + recurrence
+    # per (time point, component): the projection's 2d flops run on the matrix cores, the cosine and the
+    # recurrence (difference + fused multiply-add: 3 flops) on the vector units; the kernel is bound by
+    # whichever of the two pipes is busier for the shape (wide d: matrix cores), and the line names that one
+    elements = units * w.M * w.F
     ms = prof["ms_dp1d"] / max(1, prof["launches_dp1d"])
-    achieved = units * flops_per_unit / (ms * 1e-3) / 1e12
+    valu_tflops = elements * (COS_FLOPS + 3.0) / (ms * 1e-3) / 1e12
+    mfma_tflops = elements * 2.0 * w.d / (ms * 1e-3) / 1e12
+    valu_frac, mfma_frac = valu_tflops / VALU_FP32_UNPACKED_TFLOPS, mfma_tflops / MFMA_FP32_PEAK_TFLOPS
     gram_pairs = w.N * w.N if ((w.N + 63) // 64) * ((w.N + 63) // 64 + 1) // 2 < 512 else w.N * (w.N + 1) / 2
     gms = prof["ms_gram"] / max(1, prof["launches_gram"])
+    by_mfma = mfma_frac > valu_frac
     kernels = {
-        "dp1d": {"bound": "alu", "achieved": achieved, "peak": VALU_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                 "frac": achieved / VALU_FP32_PEAK_TFLOPS, "traffic": None, "avg_launch_ms": ms,
+        "dp1d": {"bound": "mfma" if by_mfma else "alu", "achieved": mfma_tflops if by_mfma else valu_tflops,
+                 "peak": MFMA_FP32_PEAK_TFLOPS if by_mfma else VALU_FP32_UNPACKED_TFLOPS, "unit": "TFLOP/s",
+                 "frac": max(mfma_frac, valu_frac), "traffic": None, "avg_launch_ms": ms,
                  "ms_per_step": prof["ms_dp1d"] / args.steps,
-                 "cosines_per_s": units * w.M * w.F / (ms * 1e-3)},
+                 "alu_frac": valu_frac, "alu_peak": VALU_FP32_UNPACKED_TFLOPS, "mfma_frac": mfma_frac,
+                 "cosines_per_s": elements / (ms * 1e-3)},
         "gram": {"bound": "mfma", "achieved": 2.0 * gram_pairs * ncols / (gms * 1e-3) / 1e12,
                  "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
                  "frac": 2.0 * gram_pairs * ncols / (gms * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS, "traffic": None,

@@ -31,6 +31,9 @@ def _case(seed, N, L, d, M, F, ls):
     (2, 40, 64, 8, 70),        # widest state with eight levels: more than 64 KB of LDS per workgroup
     (2, 33, 3, 16, 20),        # the largest supported number of levels
     (1, 20, 40, 13, 300),      # 13 levels on a wide state, two component slabs
+    (2, 50, 10, 3, 100),       # d well below the kernel's 32 projection rows: eleven pairs of rows read as zero
+    (2, 70, 33, 2, 130),       # odd d just above 32: the last pair of rows is half empty, three tiles
+    (3, 96, 12, 4, 64),        # whole tiles only, exactly one wavefront of components
 ])
 def test_dp1d_matches_oracle(oracle, N, L, d, M, F):
     X, W, b, ls = _case(N + L + F, N, L, d, M, F, ls=math.sqrt(d))

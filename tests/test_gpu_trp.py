@@ -35,6 +35,12 @@ def _run(X, W, Z, ls, **kw):
     (2, 2, 3, 4, 16, 16),         # one increment
     (2, 1, 3, 2, 8, 8),           # no increments
     (1, 300, 2, 6, 16, 300),      # long, six levels, two component blocks
+    (3, 30, 3, 1, 8, 12),         # one level; 29 increments in batches of eight
+    (2, 23, 4, 5, 16, 1024),      # five levels, a whole 4 KB row of the projections per sequence
+    (2, 18, 3, 7, 8, 36),         # seven levels: batches of three, sequences sharing a workgroup
+    (2, 11, 3, 9, 8, 20),         # more than eight levels: the 16-level kernel, one step per batch
+    (2, 14, 3, 12, 8, 18),        # the same with components that are no multiple of four
+    (300, 5, 2, 2, 4, 8),         # many short sequences: 150 per workgroup
 ])
 def test_trp_matches_oracle(oracle, N, L, d, M, F, Q):
     X, W, Z, ls = _case(N + L + Q, N, L, d, M, F, Q, ls=math.sqrt(d))
