@@ -80,11 +80,27 @@ const char *rfsf_ts_strerror(int code);
  *   *minimum_bytes     : smallest size accepted (one chunk of sequences).
  * Either output pointer may be NULL. The workspace holds the per-call sketch tables and
  * the time increments of the random Fourier features of one chunk of sequences
- * (Sec. 3.2, eq. (rfsf), the factors nabla phi_m) between the two kernels; its layout is
+ * (Sec. 3.2, eq. (rfsf), the factors nabla phi_m) between the two kernels, and, when the
+ * sequences are cut in time (rfsf_ts_time_cut), the feature rows of the pieces; its layout is
  * private.
  */
 int rfsf_ts_workspace_bytes(const rfsf_ts_shape *shape,
                             size_t *recommended_bytes, size_t *minimum_bytes);
+
+/*
+ * How rfsf_ts_features (and _ragged, _static) will cut the sequences of this shape in time. A batch of few
+ * long sequences (Sec. 4 measures 10 sequences of up to 1e5 points) cannot fill the GPU with one workgroup
+ * per sequence, so each sequence is cut into *pieces pieces of *pairs_per_piece pairs of time steps, the
+ * recurrence of Sec. 3.5, eq. (ts_rec) is run on every piece for each first tensor position 1..M, and the
+ * pieces are joined with the concatenation identity of iterated sums (the level-m block of x followed by y
+ * is the sum over j of the circular convolution of x's level-j block with y's block for positions j+1..m;
+ * a product per bin in the transform domain, where the pieces' accumulators are kept) before the final
+ * transforms. The result is the same feature map up to fp32 rounding. *pieces = 1 means no cut: more than 64 sequences,
+ * sequences too short to give every piece 32 pairs and the batch at least M+1 pieces each, order >= 2,
+ * M = 1 or M > 8, or a shape outside the tuned kernels. A function of the shape alone (host code, no GPU
+ * work); either output pointer may be NULL. Returns the shape check's code.
+ */
+int rfsf_ts_time_cut(const rfsf_ts_shape *shape, int32_t *pieces, int64_t *pairs_per_piece);
 
 /*
  * RFSF-TS feature map (Sec. 3.5, eqs. (cs), (ts_def), (ts), (ts_rec), order p = shape->order, on

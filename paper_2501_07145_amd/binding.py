@@ -56,6 +56,8 @@ def load_library():
     vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
     lib.rfsf_ts_strerror.restype = ctypes.c_char_p
     lib.rfsf_ts_strerror.argtypes = [ctypes.c_int]
+    lib.rfsf_ts_time_cut.restype = ctypes.c_int
+    lib.rfsf_ts_time_cut.argtypes = [ctypes.POINTER(_Shape), ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)]
     lib.rfsf_ts_workspace_bytes.restype = ctypes.c_int
     lib.rfsf_ts_workspace_bytes.argtypes = [ctypes.POINTER(_Shape), ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.rfsf_ts_features.restype = ctypes.c_int
@@ -127,6 +129,15 @@ def rfsf_ts_workspace_bytes(N: int, L: int, d: int, M: int, F: int, D: int, rff_
     rec, mn = ctypes.c_size_t(0), ctypes.c_size_t(0)
     _check(load_library().rfsf_ts_workspace_bytes(ctypes.byref(shp), ctypes.byref(rec), ctypes.byref(mn)))
     return int(rec.value), int(mn.value)
+
+
+def rfsf_ts_time_cut(N: int, L: int, d: int, M: int, F: int, D: int, order: int = 1):
+    """(pieces, pairs_per_piece): how rfsf_ts_features cuts the sequences of this shape in time
+    (pieces = 1: not at all)."""
+    shp = _Shape(N, L, d, M, F, D, 1 + M * D, 0, int(order))
+    pieces, pairs = ctypes.c_int32(0), ctypes.c_int64(0)
+    _check(load_library().rfsf_ts_time_cut(ctypes.byref(shp), ctypes.byref(pieces), ctypes.byref(pairs)))
+    return int(pieces.value), int(pairs.value)
 
 
 def feature_row_stride(M: int, D: int) -> int:

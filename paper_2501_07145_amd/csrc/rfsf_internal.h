@@ -7,6 +7,23 @@
 
 namespace rfsf {
 
+// A launch of the tuned sketch kernels may cut every sequence into `pieces` pieces of `pairs` pairs of time
+// steps each (workgroup v then owns piece v % pieces of sequence v / pieces and row v of its output), and may
+// run only the first levels of increment rows that hold `row_levels` levels (the pointers to the increments
+// and the tables are then advanced to the first level to run). `mode` 1: instead of the features, the
+// accumulators of the recurrence (levels x bins 0 .. D/2 of the transform, complex) are written to row v of
+// `spectra`; `mode` 2: no time step is run, the accumulators are read from `spectra` and turned into
+// features (the final transforms).
+struct TimeCut {
+    int pieces, row_levels;
+    int64_t pairs;
+    float2 *spectra;
+    int mode;
+    static TimeCut whole(int64_t L, int M) { return {1, M, (L + 1) / 2, nullptr, 0}; }
+};
+constexpr int kMaxCutLevels = 8;                       // the tuned kernels run at most eight levels
+struct PieceRows { const float2 *rows[kMaxCutLevels]; };
+
 // Increment workspace: row g = n * L + t holds, for every level m, the 2F numbers
 // phi_m(x_{t+1}) - phi_m(x_t) of sequence n; rows with t = L-1 exist but are never read.
 // Element (g, m, a) sits at ((g * M + m) * 2F + a).
@@ -29,10 +46,18 @@ hipError_t launch_rff_increments(const float *X, const float *W, const float *si
 // `state` is scratch for the generic kernel: sketch_fft_scan_state_bytes (accumulators, and the work buffers
 // when they do not fit in LDS).
 // `table` (sketch_fft_scan_table_bytes, filled by launch_pack_tables once per call) feeds the tuned kernel.
+// `cut` (tuned kernels only): how the launch cuts the sequences in time and which levels of the increment rows
+// it runs; TimeCut::whole(L, M) for the plain case.
 hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
                                   const uint32_t *table, int64_t n_seq, int64_t L, const int64_t *lengths, int M, int F,
                                   int D, int Dout, int order, float *out, int64_t ld_out, float *state,
-                                  hipStream_t stream);
+                                  hipStream_t stream, TimeCut cut);
+// Joins the pieces of a launch series that cut the sequences in time (csrc/join_pieces.hip).
+// pieces_of_start.rows[a]: accumulators written by the launch that ran levels a+1 .. M (row = sequence *
+// pieces + piece, M-a levels of `bins` complex numbers each). Writes M levels of `bins` numbers per sequence
+// to `joined`.
+hipError_t launch_join_pieces(const PieceRows &pieces_of_start, int64_t n_seq, int pieces, int M, int bins,
+                              float2 *joined, hipStream_t stream);
 hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int F, int D, int Dout,
                               uint32_t *table, hipStream_t stream);
 bool sketch_fft_scan_is_tuned(int M, int F, int D);

@@ -80,12 +80,53 @@ int check_shape(const rfsf_ts_shape *s)
     return RFSF_OK;
 }
 
-// Bytes of workspace one sequence needs: its increment rows plus its accumulator state.
+// Few long sequences (the shape of the paper's sequence-length runs, Sec. 4: N = 10, L up to 1e5) would keep one
+// workgroup per sequence busy and the rest of the chip idle. They are cut in time instead: `pieces` pieces of
+// `pairs` pairs of steps per sequence, the sketch kernel launched on every piece once per first tensor
+// position (M launches with M, M-1, .. 1 levels: (M+1)/2 times the work), the pieces joined by
+// csrc/join_pieces.hip and turned into features by one more launch. A function of the shape alone, so that
+// every entry point and every workspace size computes the same sums in the same order. Signature order 1 and
+// the tuned kernels only. Measured (M = 5; D = 100, 256, 1024; L = 1e3, 1e4): up to 64 sequences every cut
+// into about 1024 / N pieces of at least 32 pairs wins (1.3x at N = 64 .. 30x at N = 1), around 100 sequences
+// it is a draw, from 128 on it loses; no cut unless it brings at least M + 1 pieces; at most 128 pieces (they
+// are joined one after the other).
+struct TimeCutPlan { int pieces; int64_t pairs; };
+TimeCutPlan time_cut_plan(const rfsf_ts_shape *s)
+{
+    const int64_t all_pairs = s->L / 2;                     // L - 1 steps
+    const TimeCutPlan whole = {1, (s->L + 1) / 2};
+    const int P = transform_length(s->M, s->F, s->D);
+    if (s->order >= 2 || s->M < 2 || s->M > rfsf::kMaxCutLevels || s->N < 1 || s->N > 64 ||
+        !rfsf::sketch_fft_scan_is_tuned(s->M, s->F, P))
+        return whole;
+    int64_t want = 1024 / s->N;                             // about four workgroups per CU
+    if (want > all_pairs / 32) want = all_pairs / 32;
+    if (want > 128) want = 128;
+    if (want < s->M + 1) return whole;
+    for (int levels = 1; levels < s->M; ++levels)           // every launch of the series runs a tuned kernel
+        if (!rfsf::sketch_fft_scan_is_tuned(levels, s->F, P)) return whole;
+    const int64_t pairs = (all_pairs + want - 1) / want;
+    return {(int)((all_pairs + pairs - 1) / pairs), pairs};
+}
+// floats of one sequence's pieces: per piece and first position a the accumulators of levels a+1 .. M (bins
+// 0 .. P/2 of the transform, complex), plus the joined accumulators of the sequence
+size_t piece_floats(const rfsf_ts_shape *s, int pieces)
+{
+    const size_t bins = (size_t)transform_length(s->M, s->F, s->D) / 2 + 1;
+    size_t per_piece = 0;
+    for (int a = 0; a < s->M; ++a) per_piece += (size_t)(s->M - a) * bins * 2;
+    return per_piece * (size_t)pieces + (size_t)s->M * bins * 2;
+}
+
+// Bytes of workspace one sequence needs: its increment rows plus its state (the generic kernel's
+// accumulators; the rows of its pieces when the sequences are cut in time).
 void per_sequence_bytes(const rfsf_ts_shape *s, size_t *incr, size_t *state)
 {
     // rows of increments per sequence: L in the row layout, L rounded up to even in the pair layout
     *incr = (size_t)((s->L + 1) & ~(int64_t)1) * (size_t)s->M * 2u * (size_t)s->F * sizeof(float);
     *state = rfsf::sketch_fft_scan_state_bytes(1, s->M, transform_length(s->M, s->F, s->D), s->order == 2 ? 2 : 1);
+    const TimeCutPlan plan = time_cut_plan(s);
+    if (plan.pieces > 1) *state += sizeof(float) * piece_floats(s, plan.pieces);
 }
 
 // Fixed part: packed hash/sign table plus room for aligning the three sections.
@@ -176,6 +217,16 @@ extern "C" int rfsf_ts_workspace_bytes(const rfsf_ts_shape *shape, size_t *recom
     return RFSF_OK;
 }
 
+extern "C" int rfsf_ts_time_cut(const rfsf_ts_shape *shape, int32_t *pieces, int64_t *pairs_per_piece)
+{
+    const int rc = check_shape(shape);
+    if (rc != RFSF_OK) return rc;
+    const TimeCutPlan plan = time_cut_plan(shape);
+    if (pieces) *pieces = plan.pieces;
+    if (pairs_per_piece) *pairs_per_piece = plan.pairs;
+    return RFSF_OK;
+}
+
 namespace {
 // Body of rfsf_ts_features. `may_create` = false keeps the call free of anything that creates runtime
 // objects: the tables are then built on the caller's stream (no library-owned stream or events) and no
@@ -243,6 +294,7 @@ int features_impl(const rfsf_ts_shape *shape, const float *X, const int64_t *len
     }
 
     const float inv_ls = 1.0f / lengthscale;
+    const TimeCutPlan plan = time_cut_plan(shape);
     // the tuned consumer takes the increments in the pair layout with the signs applied, the generic one in
     // the row layout without
     const float *producer_sign = rfsf::sketch_fft_scan_is_tuned(shape->M, shape->F, P) ? sign : nullptr;
@@ -258,11 +310,37 @@ int features_impl(const rfsf_ts_shape *shape, const float *X, const int64_t *len
             if (hipStreamWaitEvent(stream, side.done, 0) != hipSuccess) return fail();
             tables_on_side = false;
         }
-        {
+        const int64_t *chunk_lengths = lengths ? lengths + n0 : nullptr;
+        if (plan.pieces == 1) {
             rfsf::ProfileScope scope(rfsf::kSketchFftScan, stream, may_create);
-            if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, table, cnt, shape->L, lengths ? lengths + n0 : nullptr,
+            if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, table, cnt, shape->L, chunk_lengths,
                                              shape->M, shape->F, P, shape->D, shape->order < 2 ? 1 : shape->order,
-                                             out + n0 * shape->ld_out, shape->ld_out, state, stream) != hipSuccess)
+                                             out + n0 * shape->ld_out, shape->ld_out, state, stream,
+                                             rfsf::TimeCut::whole(shape->L, shape->M)) != hipSuccess)
+                return RFSF_E_HIP;
+        } else {
+            // sequences cut in time: the accumulators of levels a+1 .. M of every piece for a = 0 .. M-1, the join,
+            // and the final transforms of the joined accumulators (timed as one launch of the sketch kernel class)
+            rfsf::ProfileScope scope(rfsf::kSketchFftScan, stream, may_create);
+            rfsf::PieceRows rows = {};
+            float2 *next = reinterpret_cast<float2 *>(state);
+            const size_t bins = (size_t)P / 2 + 1;
+            const size_t level_words = rfsf::sketch_fft_scan_table_bytes(shape->M, shape->F, P) / sizeof(uint32_t) / (size_t)shape->M;
+            for (int a = 0; a < shape->M; ++a) {
+                const int levels = shape->M - a;
+                rows.rows[a] = next;
+                if (rfsf::launch_sketch_fft_scan(dphi + (size_t)a * 4 * shape->F, hash, sign, table + (size_t)a * level_words,
+                                                 cnt, shape->L, chunk_lengths, levels, shape->F, P, shape->D, 1,
+                                                 out + n0 * shape->ld_out, shape->ld_out, nullptr, stream,
+                                                 rfsf::TimeCut{plan.pieces, shape->M, plan.pairs, next, 1}) != hipSuccess)
+                    return RFSF_E_HIP;
+                next += (size_t)cnt * plan.pieces * levels * bins;
+            }
+            if (rfsf::launch_join_pieces(rows, cnt, plan.pieces, shape->M, (int)bins, next, stream) != hipSuccess)
+                return RFSF_E_HIP;
+            if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, table, cnt, shape->L, chunk_lengths, shape->M, shape->F, P,
+                                             shape->D, 1, out + n0 * shape->ld_out, shape->ld_out, nullptr, stream,
+                                             rfsf::TimeCut{1, shape->M, (shape->L + 1) / 2, next, 2}) != hipSuccess)
                 return RFSF_E_HIP;
         }
     }

@@ -341,32 +341,34 @@ hipError_t launch_pack_tables(const int32_t *hash, const float *sign, int M, int
 hipError_t launch_sketch_fft_scan(const float *dphi, const int32_t *hash, const float *sign,
                                   const uint32_t *table, int64_t n_seq, int64_t L, const int64_t *lengths, int M, int F,
                                   int D, int Dout, int order, float *out, int64_t ld_out, float *state,
-                                  hipStream_t stream)
+                                  hipStream_t stream, TimeCut cut)
 {
     if (n_seq == 0) return hipSuccess;
+    if (cut.pieces < 1 || cut.pairs < 1 || cut.row_levels < M || n_seq * cut.pieces > 0x7fffffffLL) return hipErrorInvalidValue;
     int log2D = 0;
     while ((1 << log2D) < D) ++log2D;
     if (sketch_fft_scan_is_tuned(M, F, D)) {
         switch (D) {
-            case 100: return tuned::dispatch_levels_100(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
-            case 200: return tuned::dispatch_levels_200(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
-            case 500: return tuned::dispatch_levels_500(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
-            case 1000: return tuned::dispatch_levels_1000(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
-            case 2048: return tuned::dispatch_levels_2048(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            case 100: return tuned::dispatch_levels_100(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
+            case 200: return tuned::dispatch_levels_200(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
+            case 500: return tuned::dispatch_levels_500(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
+            case 1000: return tuned::dispatch_levels_1000(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
+            case 2048: return tuned::dispatch_levels_2048(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
             default: break;
         }
         switch (log2D) {
-            case 6: return tuned::dispatch_levels_6(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
-            case 7: return tuned::dispatch_levels_7(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
-            case 8: return tuned::dispatch_levels_8(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
-            case 9: return tuned::dispatch_levels_9(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
-            case 10: return tuned::dispatch_levels_10(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
-            case 12: return tuned::dispatch_levels_12(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
-            case 13: return tuned::dispatch_levels_13(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            case 6: return tuned::dispatch_levels_6(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
+            case 7: return tuned::dispatch_levels_7(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
+            case 8: return tuned::dispatch_levels_8(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
+            case 9: return tuned::dispatch_levels_9(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
+            case 10: return tuned::dispatch_levels_10(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
+            case 12: return tuned::dispatch_levels_12(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
+            case 13: return tuned::dispatch_levels_13(M, order, dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
             default: return hipErrorInvalidValue;
         }
     }
     if (order > 2) return hipErrorInvalidValue;           // order 3 exists in the tuned kernel only
+    if (cut.pieces != 1 || cut.row_levels != M || cut.mode != 0) return hipErrorInvalidValue;      // and so do cuts in time
     const bool in_global = generic_in_global(D, order);
     const size_t lds = in_global ? 0 : generic_lds_bytes(D, order);
     static size_t lds_granted = 0;        // per process; raising the limit is idempotent

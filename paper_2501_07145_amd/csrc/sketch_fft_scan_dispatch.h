@@ -10,7 +10,7 @@ namespace tuned {
 
 #define RFSF_DECLARE_DISPATCH(LOG2D)                                                                       \
     hipError_t dispatch_levels_##LOG2D(int M, int order, const float *dphi, const uint32_t *table, int64_t n_seq,     \
-                                       int64_t L, const int64_t *lengths, int F, int Dout, float *out, int64_t ld_out, hipStream_t stream);
+                                       int64_t L, const int64_t *lengths, int F, int Dout, float *out, int64_t ld_out, hipStream_t stream, TimeCut cut);
 RFSF_DECLARE_DISPATCH(6)
 RFSF_DECLARE_DISPATCH(7)
 RFSF_DECLARE_DISPATCH(8)

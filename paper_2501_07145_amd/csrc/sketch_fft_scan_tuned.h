@@ -576,7 +576,7 @@ template <int LOG2D, int M, int ORDER, int NTR>
 __global__ __launch_bounds__(64 * NTR)
     __attribute__((amdgpu_waves_per_eu(kernel_min_waves<LOG2D, M>(), kernel_min_waves<LOG2D, M>() > 4 ? 8 : 4))) void sketch_fft_scan_kernel(
     const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L,
-    const int64_t *__restrict__ lengths, int F, int Dout, float *__restrict__ out, int64_t ld_out)
+    const int64_t *__restrict__ lengths, int F, int Dout, float *__restrict__ out, int64_t ld_out, TimeCut cut)
 {
     using P = Plan<LOG2D>;
     // kStream: the workgroup's NTR transforms of an iteration are the next NTR (pair group, level) items of the
@@ -609,16 +609,20 @@ __global__ __launch_bounds__(64 * NTR)
     float2 *wave_lds = lds + (size_t)wv * P::FPW * PS;
     float2 *my_slot = wave_lds + slot_id * PS;
     char *my_slot_bytes = reinterpret_cast<char *>(my_slot);
-    const int64_t n = blockIdx.x;
+    // the workgroup's row of out, its sequence and its piece of that sequence (one piece: the whole sequence)
+    const int64_t row_id = blockIdx.x;
+    const int64_t n = cut.pieces == 1 ? row_id : row_id / cut.pieces, piece = row_id - n * cut.pieces;
     // this sequence's own number of points (variable-length batch: X is padded to L points, the steps beyond a
     // sequence's length do not exist); out-of-range entries are clamped, they are never used as addresses
     const int64_t Ln = lengths ? (lengths[n] < 1 ? 1 : (lengths[n] > L ? L : lengths[n])) : L;
-    const int64_t T = Ln - 1;
+    // the piece's own steps: 2 * cut.pairs of them from its first one on, fewer (or none) at the sequence's end
+    const int64_t steps_left = Ln - 1 - 2 * piece * cut.pairs;
+    const int64_t T = cut.mode == 2 || steps_left < 0 ? 0 : (steps_left < 2 * cut.pairs ? steps_left : 2 * cut.pairs);
     const int64_t pairs = (T + 1) / 2;
     // pair p of level l: 2F float2 at seq + l * 2 * twoF + p * pf (pair layout of the producing kernel, Lp / 2
     // pair slots per sequence with Lp = L rounded up to even)
-    const int64_t pf = (int64_t)M * 2 * twoF;
-    const float *seq = dphi + n * ((L + 1) / 2) * pf;
+    const int64_t pf = (int64_t)cut.row_levels * 2 * twoF;
+    const float *seq = dphi + (n * ((L + 1) / 2) + piece * cut.pairs) * pf;
     const TableLayout tl = table_layout(D, P::GF, twoF);
     const int nload = staged(twoF) / 128;                    // direct loads per pair, 128 coordinates each
     // one level per wavefront for good: its increments, table and number of fold rounds
@@ -636,6 +640,21 @@ __global__ __launch_bounds__(64 * NTR)
     for (int b = 0; b < BPT; ++b)
 #pragma unroll
         for (int l = 0; l < M; ++l) A[b][l] = make_float2(0.f, 0.f);
+    // accumulators kept outside the kernel (sequences cut in time): M levels of bins 0 .. D/2 per row
+    float2 *spectra_row = cut.mode != 0 ? cut.spectra + row_id * (int64_t)(M * (D / 2 + 1)) : nullptr;
+    if (cut.mode == 2) {
+#pragma unroll
+        for (int b = 0; b < BPT; ++b) {
+            const int f = tid + NT * b;
+            if (f < NB) {
+#pragma unroll
+                for (int l = 0; l < M; ++l) {
+                    const float2 *sp = spectra_row + l * (D / 2 + 1);
+                    A[b][l] = kPack && f == 0 ? make_float2(sp[0].x, sp[D / 2].x) : sp[f];
+                }
+            }
+        }
+    }
 
     // Staging: pair pair0 + s of level lvl goes to slot s of the wavefront, 128 coordinates (1 KB) per
     // instruction, lane i supplying coordinates 2i and 2i+1. Pairs beyond the last one (final group only) are redirected to the last pair and
@@ -854,6 +873,27 @@ __global__ __launch_bounds__(64 * NTR)
     }
     if (kEarly) __syncthreads();
 
+    if (cut.mode == 1) {                                     // a piece of a sequence: its accumulators are the result
+#pragma unroll
+        for (int b = 0; b < BPT; ++b) {
+            const int f = tid + NT * b;
+            if (f < NB) {
+#pragma unroll
+                for (int l = 0; l < M; ++l) {
+                    float2 *sp = spectra_row + l * (D / 2 + 1);
+                    const float2 y = A[b][l];
+                    if (kPack && f == 0) {                   // bins 0 and D/2, both real
+                        sp[0] = make_float2(y.x, 0.f);
+                        sp[D / 2] = make_float2(y.y, 0.f);
+                    } else {
+                        sp[f] = y;
+                    }
+                }
+            }
+        }
+        return;
+    }
+
     // Phi_m = Re(FFT(conj Y_m)) / D with Y_m the Hermitian extension of A_m; slot 0 of transform m of the workgroup.
 #pragma unroll
     for (int b = 0; b < BPT; ++b) {
@@ -877,7 +917,7 @@ __global__ __launch_bounds__(64 * NTR)
     if (wv < M) {                                            // (always, unless streaming)
         fft.run(my_slot);
         transform_fence<P>();
-        float *row = out + n * ld_out;
+        float *row = out + row_id * ld_out;
         if (tid == 0) row[0] = 1.0f;
         const float invD = 1.0f / (float)D;
         // Dout buckets per level. Dout == D: the transform was circular in D already. Dout < D (a bucket

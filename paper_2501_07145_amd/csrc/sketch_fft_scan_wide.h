@@ -41,7 +41,7 @@ __host__ __device__ constexpr size_t wide_lds_bytes(int S, int M, int F)
 template <int LOG2S, int M, int ORDER, int NTR>
 __global__ __launch_bounds__(64 * (1 << LOG2S) * NTR) __attribute__((amdgpu_waves_per_eu(4, 4))) void sketch_fft_scan_wide_kernel(
     const float *__restrict__ dphi, const uint32_t *__restrict__ table, int64_t L,
-    const int64_t *__restrict__ lengths, int F, int Dout, float *__restrict__ out, int64_t ld_out)
+    const int64_t *__restrict__ lengths, int F, int Dout, float *__restrict__ out, int64_t ld_out, TimeCut cut)
 {
     using P = Plan<10>;                                     // the transform each wavefront runs
     constexpr int S = 1 << LOG2S, DH = 1024, DF = S * DH, NT = 64 * S * NTR;
@@ -60,12 +60,15 @@ __global__ __launch_bounds__(64 * (1 << LOG2S) * NTR) __attribute__((amdgpu_wave
     char *lvl_bytes = reinterpret_cast<char *>(lvl_slot);
     float2 *sub_slot = lvl_slot + res * P::PD;
     float2 *stage = lvl_slot + kWideStageBase;
-    const int64_t n = blockIdx.x;
+    // row of out, sequence, piece of the sequence and the piece's own steps, as in the kernel for shorter transforms
+    const int64_t row_id = blockIdx.x;
+    const int64_t n = cut.pieces == 1 ? row_id : row_id / cut.pieces, piece = row_id - n * cut.pieces;
     const int64_t Ln = lengths ? (lengths[n] < 1 ? 1 : (lengths[n] > L ? L : lengths[n])) : L;
-    const int64_t T = Ln - 1;
+    const int64_t steps_left = Ln - 1 - 2 * piece * cut.pairs;
+    const int64_t T = cut.mode == 2 || steps_left < 0 ? 0 : (steps_left < 2 * cut.pairs ? steps_left : 2 * cut.pairs);
     const int64_t pairs = (T + 1) / 2;
-    const int64_t pf = (int64_t)M * 2 * twoF;
-    const float *seq = dphi + n * ((L + 1) / 2) * pf;
+    const int64_t pf = (int64_t)cut.row_levels * 2 * twoF;
+    const float *seq = dphi + (n * ((L + 1) / 2) + piece * cut.pairs) * pf;
     const TableLayout tl = table_layout(DF, 64, twoF);
     const int nload = staged(twoF) / 128;
     const float *seq_fixed = seq + (int64_t)wvl * 2 * twoF;
@@ -80,6 +83,19 @@ __global__ __launch_bounds__(64 * (1 << LOG2S) * NTR) __attribute__((amdgpu_wave
     for (int b = 0; b < BPT; ++b)
 #pragma unroll
         for (int l = 0; l < M; ++l) A[b][l] = make_float2(0.f, 0.f);
+    // accumulators kept outside the kernel (sequences cut in time): M levels of bins 0 .. DF/2 per row
+    float2 *spectra_row = cut.mode != 0 ? cut.spectra + row_id * (int64_t)(M * (DF / 2 + 1)) : nullptr;
+    if (cut.mode == 2) {
+#pragma unroll
+        for (int b = 0; b < BPT; ++b) {
+            const int f = tid + NT * b;
+#pragma unroll
+            for (int l = 0; l < M; ++l) {
+                const float2 *sp = spectra_row + l * (DF / 2 + 1);
+                A[b][l] = f == 0 ? make_float2(sp[0].x, sp[DF / 2].x) : sp[f];
+            }
+        }
+    }
     // w^g of the thread's butterflies of the combining pass: butterfly c is number tid + NT * c of the NTR * 1024
     float2 wg[BFPT];
 #pragma unroll
@@ -248,8 +264,27 @@ __global__ __launch_bounds__(64 * (1 << LOG2S) * NTR) __attribute__((amdgpu_wave
         __syncthreads();                                    // the slots are free again
     }
 
+    if (cut.mode == 1) {                                    // a piece of a sequence: its accumulators are the result
+#pragma unroll
+        for (int b = 0; b < BPT; ++b) {
+            const int f = tid + NT * b;
+#pragma unroll
+            for (int l = 0; l < M; ++l) {
+                float2 *sp = spectra_row + l * (DF / 2 + 1);
+                const float2 a = A[b][l];
+                if (f == 0) {                               // bins 0 and DF/2 are real
+                    sp[0] = make_float2(a.x, 0.f);
+                    sp[DF / 2] = make_float2(a.y, 0.f);
+                } else {
+                    sp[f] = a;
+                }
+            }
+        }
+        return;
+    }
+
     // Phi_l = Re(FFT(conj Y_l)) / DF with Y_l the Hermitian extension of A_l, NTR levels at a time
-    float *row = out + n * ld_out;
+    float *row = out + row_id * ld_out;
     if (tid == 0) row[0] = 1.0f;
 #pragma unroll
     for (int l0 = 0; l0 < M; l0 += NTR) {
@@ -291,7 +326,7 @@ __global__ __launch_bounds__(64 * (1 << LOG2S) * NTR) __attribute__((amdgpu_wave
 
 template <int LOG2S, int M, int ORDER>
 hipError_t launch_wide(const float *dphi, const uint32_t *table, int64_t n_seq, int64_t L, const int64_t *lengths, int F, int Dout,
-                       float *out, int64_t ld_out, hipStream_t stream)
+                       float *out, int64_t ld_out, hipStream_t stream, TimeCut cut)
 {
     constexpr int S = 1 << LOG2S, NTR = wide_levels_in_flight(M);
     const size_t lds = wide_lds_bytes(S, M, F);
@@ -305,20 +340,20 @@ hipError_t launch_wide(const float *dphi, const uint32_t *table, int64_t n_seq, 
             raised = lds;
         }
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)n_seq), dim3(64 * S * NTR), lds, stream, dphi, table, L, lengths, F, Dout, out, ld_out);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(n_seq * cut.pieces)), dim3(64 * S * NTR), lds, stream, dphi, table, L, lengths, F, Dout, out, ld_out, cut);
     return hipGetLastError();
 }
 
 template <int LOG2S>
 hipError_t dispatch_wide(int M, int order, const float *dphi, const uint32_t *table, int64_t n_seq, int64_t L, const int64_t *lengths,
-                         int F, int Dout, float *out, int64_t ld_out, hipStream_t stream)
+                         int F, int Dout, float *out, int64_t ld_out, hipStream_t stream, TimeCut cut)
 {
     switch (M) {
 #define RFSF_CASE(MM)                                                                                                  \
         case MM:                                                                                                       \
-            return order == 3 ? launch_wide<LOG2S, MM, 3>(dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream)    \
-                 : order == 2 ? launch_wide<LOG2S, MM, 2>(dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream)    \
-                              : launch_wide<LOG2S, MM, 1>(dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream);
+            return order == 3 ? launch_wide<LOG2S, MM, 3>(dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut)    \
+                 : order == 2 ? launch_wide<LOG2S, MM, 2>(dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut)    \
+                              : launch_wide<LOG2S, MM, 1>(dphi, table, n_seq, L, lengths, F, Dout, out, ld_out, stream, cut);
         RFSF_CASE(1) RFSF_CASE(2) RFSF_CASE(3) RFSF_CASE(4) RFSF_CASE(5) RFSF_CASE(6) RFSF_CASE(7) RFSF_CASE(8)
 #undef RFSF_CASE
         default: return hipErrorInvalidValue;

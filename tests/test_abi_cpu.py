@@ -144,3 +144,23 @@ def test_binding_refuses_host_tensors():
         binding.rfsf_ts_features(X, W, h, s, 1.0, 8)
     with pytest.raises(ValueError):
         binding.rfsf_ts_gram(torch.zeros(3, 5))
+
+
+def test_time_cut_plan_is_a_function_of_the_shape():
+    """Few long sequences are cut in time, many or short ones are not; host logic only."""
+    cut = binding.rfsf_ts_time_cut
+    pieces, pairs = cut(10, 100000, 5, 5, 50, 100)          # the paper's sequence-length runs (Sec. 4)
+    assert 6 <= pieces <= 128 and pairs >= 32
+    assert pieces * pairs >= 50000 > (pieces - 1) * pairs   # the pieces cover the L/2 pairs, none is empty
+    assert cut(1, 100000, 5, 5, 50, 100)[0] == 128          # never more than 128 pieces
+    assert cut(64, 100000, 5, 5, 50, 100)[0] == 16
+    assert cut(65, 100000, 5, 5, 50, 100) == (1, 50000)     # from here on a workgroup per sequence is the better use of the chip
+    assert cut(10000, 200, 17, 5, 512, 1024) == (1, 100)
+    assert cut(10, 200, 5, 5, 50, 100) == (1, 100)          # too short for M + 1 pieces of 32 pairs
+    assert cut(10, 100000, 5, 1, 50, 100)[0] == 1           # one level: nothing to join, nothing gained
+    assert cut(10, 100000, 5, 5, 50, 100, order=2)[0] == 1  # signature order 2: no cut
+    assert cut(10, 100000, 5, 9, 50, 100)[0] == 1           # nine levels run the generic kernel
+    # the workspace grows by the pieces' accumulators and stays consistent with the minimum
+    rec, mn = binding.rfsf_ts_workspace_bytes(10, 100000, 5, 5, 50, 100)
+    rec1, mn1 = binding.rfsf_ts_workspace_bytes(10, 100000, 5, 5, 50, 100, order=2)
+    assert rec > rec1 and mn > mn1 and rec >= mn
