@@ -370,7 +370,7 @@ def bench_ts(args, name: str, steps: int, warmup: int, cpu_baseline: bool) -> di
     if cpu_baseline:
         import oracle
         from tests.parity import block_errors, gram_error
-        default_rows = {"tiny": 16, "small": 1000, "medium": 512, "long": 128, "large": 256, "paper": 100}[w.name]
+        default_rows = {"tiny": 16, "small": 1000, "medium": 512, "long": 128, "large": 256, "paper": 100, "paper_long": 2}[w.name]
         rows = min(w.N, default_rows if args.cpu_rows < 0 else args.cpu_rows)
         sel = np.linspace(0, w.N - 1, rows).round().astype(np.int64)
         Xs = inp["X"][sel]
@@ -402,7 +402,7 @@ def bench_ts(args, name: str, steps: int, warmup: int, cpu_baseline: bool) -> di
 
 
 DEFAULT_STEPS = {"tiny": (300, 50), "small": (300, 50), "medium": (20, 3), "long": (20, 3), "large": (5, 1),
-                 "paper": (20, 3)}
+                 "paper": (20, 3), "paper_long": (20, 3)}
 
 
 def main() -> int:
@@ -414,7 +414,7 @@ def main() -> int:
                     help="medium (default) is the largest configuration that runs in fp32 throughout")
     ap.add_argument("--also", default=None,
                     help="comma-separated further workloads measured after the headline one with their own default "
-                         "step counts and reported under 'other_workloads' (default: small,long,large,paper when the "
+                         "step counts and reported under 'other_workloads' (default: small,long,large,paper,paper_long when the "
                          "headline is the default medium run, none otherwise; 'none' switches it off)")
     ap.add_argument("--cpu-rows", type=int, default=-1, help="oracle sample size (-1: per-workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -433,7 +433,7 @@ def main() -> int:
     default_run = args.workload == "medium" and args.variant == "ts" and not args.normalize and \
         args.workspace_mib == 0 and args.copy_probe_mib == 0
     if args.also is None:
-        args.also = "small,long,large,paper" if default_run else "none"
+        args.also = "small,long,large,paper,paper_long" if default_run else "none"
     if args.steps is None:
         args.steps = DEFAULT_STEPS[args.workload][0]
     if args.warmup is None:

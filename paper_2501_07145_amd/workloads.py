@@ -80,6 +80,10 @@ WORKLOADS = {
     # feature and projection sizes 100, batches of 10-100 sequences of length 100 .. 1e5); its bucket
     # count is no power of two
     "paper": Workload("paper", N=100, L=1000, d=5, M=5, F=50, D=100, lengthscale=math.sqrt(5.0), kind="brownian"),
+    # the long end of the paper's sequence-length runs (Sec. 4: N = 10, L increased until memory runs out,
+    # 1e5 and more for the primal methods): few long sequences, which the library cuts in time
+    "paper_long": Workload("paper_long", N=10, L=100000, d=5, M=5, F=50, D=100, lengthscale=math.sqrt(5.0),
+                           kind="brownian"),
 }
 
 

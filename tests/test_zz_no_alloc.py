@@ -49,8 +49,8 @@ def test_static_scratch_matches_workspace_path_twice(oracle):
     inp3, dev3 = _inputs(tiny)
     ref3, got3 = _both(tiny, dev3, inp3["lengthscale"], order=2)
     assert np.array_equal(ref3, got3)
-    # fourth: 32 buckets run the generic kernel, whose accumulator state also lives in the scratch
-    gen = wl.Workload("generic", N=6, L=20, d=3, M=3, F=8, D=32, lengthscale=1.0, kind="brownian")
+    # fourth: nine levels run the generic kernel, whose accumulator state also lives in the scratch
+    gen = wl.Workload("generic", N=6, L=20, d=3, M=9, F=8, D=32, lengthscale=1.0, kind="brownian")
     inp4, dev4 = _inputs(gen)
     ref4, got4 = _both(gen, dev4, inp4["lengthscale"])
     assert np.array_equal(ref4, got4)
@@ -69,3 +69,11 @@ def test_static_scratch_rejects_what_does_not_fit():
         rfsf.rfsf_ts_features_static(X, W, h, s, 1.0, 512, out)
     assert e.value.code == -10
     assert torch.all(out == 0)
+    # fifth: three long sequences, cut in time; the accumulators of their pieces live in the scratch as well
+    cut = wl.WORKLOADS["paper"].scaled(N=3, L=1000)
+    assert rfsf.rfsf_ts_time_cut(cut.N, cut.L, cut.d, cut.M, cut.F, cut.D)[0] > 1
+    inp5, dev5 = _inputs(cut)
+    ref5, got5 = _both(cut, dev5, inp5["lengthscale"])
+    assert np.array_equal(ref5, got5)
+    want5 = oracle.features(inp5["X"], inp5["W"], inp5["hash"], inp5["sign"], inp5["lengthscale"], cut.D)
+    assert np.all(block_errors(got5, want5, cut.M, cut.D) <= FP32_BLOCK_TOL)
