@@ -96,7 +96,7 @@ int rfsf_ts_workspace_bytes(const rfsf_ts_shape *shape,
  * is the sum over j of the circular convolution of x's level-j block with y's block for positions j+1..m;
  * a product per bin in the transform domain, where the pieces' accumulators are kept) before the final
  * transforms. The result is the same feature map up to fp32 rounding. *pieces = 1 means no cut: more than 64 sequences,
- * sequences too short to give every piece 32 pairs and the batch at least M+1 pieces each, order >= 2,
+ * sequences too short to give every piece 32 pairs and the batch at least M+1 pieces each,
  * M = 1 or M > 8, or a shape outside the tuned kernels. A function of the shape alone (host code, no GPU
  * work); either output pointer may be NULL. Returns the shape check's code.
  */

@@ -85,8 +85,8 @@ int check_shape(const rfsf_ts_shape *s)
 // `pairs` pairs of steps per sequence, the sketch kernel launched on every piece once per first tensor
 // position (M launches with M, M-1, .. 1 levels: (M+1)/2 times the work), the pieces joined by
 // csrc/join_pieces.hip and turned into features by one more launch. A function of the shape alone, so that
-// every entry point and every workspace size computes the same sums in the same order. Signature order 1 and
-// the tuned kernels only. Measured (M = 5; D = 100, 256, 1024; L = 1e3, 1e4): up to 64 sequences every cut
+// every entry point and every workspace size computes the same sums in the same order. The tuned kernels only
+// (any signature order they have: a step's truncated exponential is a factor of the product over steps either way). Measured (M = 5; D = 100, 256, 1024; L = 1e3, 1e4): up to 64 sequences every cut
 // into about 1024 / N pieces of at least 32 pairs wins (1.3x at N = 64 .. 30x at N = 1), around 100 sequences
 // it is a draw, from 128 on it loses; no cut unless it brings at least M + 1 pieces; at most 128 pieces (they
 // are joined one after the other).
@@ -96,7 +96,7 @@ TimeCutPlan time_cut_plan(const rfsf_ts_shape *s)
     const int64_t all_pairs = s->L / 2;                     // L - 1 steps
     const TimeCutPlan whole = {1, (s->L + 1) / 2};
     const int P = transform_length(s->M, s->F, s->D);
-    if (s->order >= 2 || s->M < 2 || s->M > rfsf::kMaxCutLevels || s->N < 1 || s->N > 64 ||
+    if (s->order > 3 || s->M < 2 || s->M > rfsf::kMaxCutLevels || s->N < 1 || s->N > 64 ||
         !rfsf::sketch_fft_scan_is_tuned(s->M, s->F, P))
         return whole;
     int64_t want = 1024 / s->N;                             // about four workgroups per CU
@@ -323,6 +323,7 @@ int features_impl(const rfsf_ts_shape *shape, const float *X, const int64_t *len
             // and the final transforms of the joined accumulators (timed as one launch of the sketch kernel class)
             rfsf::ProfileScope scope(rfsf::kSketchFftScan, stream, may_create);
             rfsf::PieceRows rows = {};
+            const int order = shape->order < 2 ? 1 : shape->order;
             float2 *next = reinterpret_cast<float2 *>(state);
             const size_t bins = (size_t)P / 2 + 1;
             const size_t level_words = rfsf::sketch_fft_scan_table_bytes(shape->M, shape->F, P) / sizeof(uint32_t) / (size_t)shape->M;
@@ -330,7 +331,7 @@ int features_impl(const rfsf_ts_shape *shape, const float *X, const int64_t *len
                 const int levels = shape->M - a;
                 rows.rows[a] = next;
                 if (rfsf::launch_sketch_fft_scan(dphi + (size_t)a * 4 * shape->F, hash, sign, table + (size_t)a * level_words,
-                                                 cnt, shape->L, chunk_lengths, levels, shape->F, P, shape->D, 1,
+                                                 cnt, shape->L, chunk_lengths, levels, shape->F, P, shape->D, order,
                                                  out + n0 * shape->ld_out, shape->ld_out, nullptr, stream,
                                                  rfsf::TimeCut{plan.pieces, shape->M, plan.pairs, next, 1}) != hipSuccess)
                     return RFSF_E_HIP;
@@ -339,7 +340,7 @@ int features_impl(const rfsf_ts_shape *shape, const float *X, const int64_t *len
             if (rfsf::launch_join_pieces(rows, cnt, plan.pieces, shape->M, (int)bins, next, stream) != hipSuccess)
                 return RFSF_E_HIP;
             if (rfsf::launch_sketch_fft_scan(dphi, hash, sign, table, cnt, shape->L, chunk_lengths, shape->M, shape->F, P,
-                                             shape->D, 1, out + n0 * shape->ld_out, shape->ld_out, nullptr, stream,
+                                             shape->D, order, out + n0 * shape->ld_out, shape->ld_out, nullptr, stream,
                                              rfsf::TimeCut{1, shape->M, (shape->L + 1) / 2, next, 2}) != hipSuccess)
                 return RFSF_E_HIP;
         }

@@ -64,12 +64,18 @@ def test_cut_sequences_of_different_lengths(oracle):
     assert np.array_equal(got[4], np.concatenate([[1.0], np.zeros(M * D)]).astype(np.float32))
 
 
-def test_shapes_that_are_not_cut_still_run(oracle):
-    """Signature order 2 has no cut."""
-    N, L, d, M, F, D = 2, 600, 3, 3, 16, 64
-    assert rfsf.rfsf_ts_time_cut(N, L, d, M, F, D, order=2)[0] == 1
-    assert rfsf.rfsf_ts_time_cut(N, L, d, M, F, D)[0] > 1
-    X, W, hash_, sign, ls = _case(5, N, L, d, M, F, D)
-    got = _gpu(X, W, hash_, sign, ls, D, order=2)
-    want = oracle.features_order(X, W, hash_, sign, ls, D, 2)
-    assert np.all(block_errors(got, want, M, D) <= FP32_BLOCK_TOL)
+@pytest.mark.parametrize("order,N,L,d,M,F,D", [
+    (2, 2, 600, 3, 3, 16, 64),
+    (2, 3, 500, 5, 5, 50, 100),
+    (3, 2, 700, 3, 4, 24, 128),
+    (3, 1, 451, 4, 5, 96, 1024),
+])
+def test_cut_sequences_of_higher_signature_order(oracle, order, N, L, d, M, F, D):
+    """A time step used up to `order` times in a row never spans two pieces, so the pieces join the same way."""
+    assert rfsf.rfsf_ts_time_cut(N, L, d, M, F, D, order=order)[0] > M
+    X, W, hash_, sign, ls = _case(5 + order + L, N, L, d, M, F, D)
+    got = _gpu(X, W, hash_, sign, ls, D, order=order)
+    want = oracle.features_order(X, W, hash_, sign, ls, D, order)
+    err = block_errors(got, want, M, D)
+    print(f"order {order} N={N} L={L} M={M} D={D}: block errors {err}")
+    assert np.all(err <= FP32_BLOCK_TOL)

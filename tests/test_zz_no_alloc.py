@@ -57,6 +57,15 @@ def test_static_scratch_matches_workspace_path_twice(oracle):
     want4 = oracle.features(inp4["X"], inp4["W"], inp4["hash"], inp4["sign"], inp4["lengthscale"], gen.D)
     assert np.all(block_errors(got4, want4, gen.M, gen.D) <= FP32_BLOCK_TOL)
 
+    # fifth: three long sequences, cut in time; the accumulators of their pieces live in the scratch as well
+    cut = wl.WORKLOADS["paper"].scaled(N=3, L=1000)
+    assert rfsf.rfsf_ts_time_cut(cut.N, cut.L, cut.d, cut.M, cut.F, cut.D)[0] > 1
+    inp5, dev5 = _inputs(cut)
+    ref5, got5 = _both(cut, dev5, inp5["lengthscale"])
+    assert np.array_equal(ref5, got5)
+    want5 = oracle.features(inp5["X"], inp5["W"], inp5["hash"], inp5["sign"], inp5["lengthscale"], cut.D)
+    assert np.all(block_errors(got5, want5, cut.M, cut.D) <= FP32_BLOCK_TOL)
+
 
 def test_static_scratch_rejects_what_does_not_fit():
     # one sequence of the long workload has 2000 * 4 * 512 * 4 B = 16 MB of increments: fits; 20000 steps do not
@@ -69,11 +78,3 @@ def test_static_scratch_rejects_what_does_not_fit():
         rfsf.rfsf_ts_features_static(X, W, h, s, 1.0, 512, out)
     assert e.value.code == -10
     assert torch.all(out == 0)
-    # fifth: three long sequences, cut in time; the accumulators of their pieces live in the scratch as well
-    cut = wl.WORKLOADS["paper"].scaled(N=3, L=1000)
-    assert rfsf.rfsf_ts_time_cut(cut.N, cut.L, cut.d, cut.M, cut.F, cut.D)[0] > 1
-    inp5, dev5 = _inputs(cut)
-    ref5, got5 = _both(cut, dev5, inp5["lengthscale"])
-    assert np.array_equal(ref5, got5)
-    want5 = oracle.features(inp5["X"], inp5["W"], inp5["hash"], inp5["sign"], inp5["lengthscale"], cut.D)
-    assert np.all(block_errors(got5, want5, cut.M, cut.D) <= FP32_BLOCK_TOL)
