@@ -410,7 +410,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 300 for tiny/small, 20 for medium/long, 5 for large)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default: 50 / 3 / 1)")
-    ap.add_argument("--workload", default="medium", choices=["tiny", "small", "medium", "long", "large", "paper"],
+    ap.add_argument("--workload", default="medium", choices=["tiny", "small", "medium", "long", "large", "paper", "paper_long"],
                     help="medium (default) is the largest configuration that runs in fp32 throughout")
     ap.add_argument("--also", default=None,
                     help="comma-separated further workloads measured after the headline one with their own default "
