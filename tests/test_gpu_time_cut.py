@@ -79,3 +79,17 @@ def test_cut_sequences_of_higher_signature_order(oracle, order, N, L, d, M, F, D
     err = block_errors(got, want, M, D)
     print(f"order {order} N={N} L={L} M={M} D={D}: block errors {err}")
     assert np.all(err <= FP32_BLOCK_TOL)
+
+
+def test_cut_sequences_through_the_smallest_workspace(oracle):
+    """One sequence per launch series: the plan does not depend on the workspace, the result does not either."""
+    N, L, d, M, F, D = 3, 700, 3, 3, 20, 64
+    assert rfsf.rfsf_ts_time_cut(N, L, d, M, F, D)[0] > M
+    X, W, hash_, sign, ls = _case(11, N, L, d, M, F, D)
+    rec, mn = rfsf.rfsf_ts_workspace_bytes(N, L, d, M, F, D)
+    assert mn < rec
+    small = _gpu(X, W, hash_, sign, ls, D, workspace=torch.empty(mn, dtype=torch.uint8, device="cuda"))
+    full = _gpu(X, W, hash_, sign, ls, D, workspace=torch.empty(rec, dtype=torch.uint8, device="cuda"))
+    assert np.array_equal(small, full)
+    want = oracle.features(X, W, hash_, sign, ls, D)
+    assert np.all(block_errors(small, want, M, D) <= FP32_BLOCK_TOL)
