@@ -224,7 +224,7 @@ int rfsf_ts_normalize_features(float *Phi, int64_t N, int64_t ld, int32_t M, int
  * and out[n, 0] = 1, out[n, 1 + (m-1) F + i] = Phi_m[i]  (1 + M*F columns).
  *   X [N, L, d], W [M, d, F], bias [M, F] (uniform on [0, 2 pi) for an unbiased kernel estimate),
  *   out [N, ld_out], ld_out >= 1 + M*F; all float32 device pointers. No workspace is needed.
- * Limits of this build: d <= 64, M <= 16 (RFSF_E_UNSUPPORTED beyond). N = 0 is a no-op; L = 1 gives
+ * Limits of this build: d <= 64, M <= 16, d*F*4 < 2^31 (RFSF_E_UNSUPPORTED beyond). N = 0 is a no-op; L = 1 gives
  * (1, 0, ..., 0).
  */
 int rfsf_dp1d_features(int64_t N, int64_t L, int32_t d, int32_t M, int32_t F,

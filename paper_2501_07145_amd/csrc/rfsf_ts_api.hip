@@ -462,6 +462,7 @@ extern "C" int rfsf_dp1d_features(int64_t N, int64_t L, int32_t d, int32_t M, in
     if (ld_out < 1 + (int64_t)M * F) return RFSF_E_BAD_STRIDE;
     if (!(lengthscale > 0.0f) || !std::isfinite(lengthscale)) return RFSF_E_BAD_LENGTHSCALE;
     if (d > 64 || M > 16 || (F + 255) / 256 > 65535) return RFSF_E_UNSUPPORTED;
+    if ((int64_t)d * F * 4 > 0x7fffffffLL) return RFSF_E_UNSUPPORTED;     // a level of W is addressed with 32-bit byte offsets
     if (N == 0) return RFSF_OK;
     if (!X || !W || !bias || !out) return RFSF_E_NULLPTR;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);

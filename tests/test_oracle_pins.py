@@ -351,3 +351,33 @@ def test_order_p_single_increment(oracle):
     np.testing.assert_allclose(got[:, 0, 0], u[:, 0], rtol=0, atol=1e-14)
     np.testing.assert_allclose(got[:, 1, 0], u[:, 0] * u[:, 1] / 2.0, rtol=0, atol=1e-14)
     assert np.all(got[:, 2] == 0.0) and np.all(got[:, :, 1:] == 0.0)
+
+
+# ---------------------------------------------------------------- concatenation of sequences
+@pytest.mark.parametrize("order", [1, 2, 3])
+def test_features_of_a_sequence_cut_in_two(oracle, order):
+    """Sec. 3.5 eq. (ts_rec): the index tuples of a sequence x followed by y split by how many indices fall
+    into x, so level m of the whole is  S^{(1..m)}(y) + S^{(1..m)}(x) + sum_{j=1}^{m-1} S^{(1..j)}(x) * S^{(j+1..m)}(y)
+    with * the circular convolution over the buckets and S^{(a..b)} the features computed with the maps
+    (W, hash, sign) of tensor positions a .. b. The GPU library relies on this to cut long sequences in time;
+    here the oracle is held to it (the convolution is written out directly, the pieces share the boundary point)."""
+    N, L, d, M, F, D = 2, 11, 3, 4, 5, 7
+    X, W, hash_, sign, ls = _case(41, N, L, d, M, F, D)
+    feats = (lambda *a: oracle.features(*a)) if order == 1 else (lambda *a: oracle.features_order(*a, order))
+    whole = feats(X, W, hash_, sign, ls, D)[:, 1:].reshape(N, M, D)
+    for cut in (1, 4, 9):
+        x, y = X[:, :cut + 1], X[:, cut:]
+
+        def S(piece, a, b):                                     # positions a .. b (1-based), blocks [N, b-a+1, D]
+            return feats(piece, W[a - 1:b], hash_[a - 1:b], sign[a - 1:b], ls, D)[:, 1:].reshape(N, b - a + 1, D)
+
+        for m in range(1, M + 1):
+            want = S(y, 1, m)[:, m - 1] + S(x, 1, m)[:, m - 1]
+            for j in range(1, m):
+                left, right = S(x, 1, j)[:, j - 1], S(y, j + 1, m)[:, m - j - 1]
+                conv = np.zeros((N, D))
+                for p in range(D):
+                    for q in range(D):
+                        conv[:, (p + q) % D] += left[:, p] * right[:, q]
+                want = want + conv
+            np.testing.assert_allclose(whole[:, m - 1], want, rtol=1e-9, atol=1e-12)
