@@ -282,19 +282,19 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 template <int KSTEPS, bool PAIRED>     // ceil(d / 2) padded: channels 2*KSTEPS
 __global__ __launch_bounds__(256) void rff_increments_mfma(
     const float *__restrict__ X, const float *__restrict__ W, const float *__restrict__ sign, float inv_lengthscale,
-    float scale, int64_t rows, int64_t L, int64_t Lp, int d, int M, int F, int64_t rows_per_block, int64_t nblk,
-    int slab_fastest, float *__restrict__ dphi)
+    float scale, int64_t rows, int64_t L, int64_t Lp, int d, int M, int F, int64_t rows_per_block,
+    float *__restrict__ dphi)
 {
     constexpr int KP = 2 * KSTEPS;              // padded channel count
     constexpr int XS = KP | 1;                  // odd LDS row stride: conflict-free A reads
     __shared__ float xs[2 * kRowsPerTile * XS];
-    // Block order. With many (level, frequency slab) pairs per row range the slab index runs fastest:
-    // the workgroups that write the same rows are dispatched together, which keeps the writes of one
-    // DRAM page close in time. With few of them the row range runs fastest.
+    // Block order: the (level, frequency slab) index runs fastest, so that the workgroups that write the
+    // same rows are dispatched together, which keeps the writes of one DRAM page close in time (also with
+    // few slabs: four slabs of 1000 short sequences run 17 % faster this way than row range first).
     const int fblocks = (F + 127) / 128;
     const int nslab = M * fblocks;
-    const int slab = slab_fastest ? (int)(blockIdx.x % nslab) : (int)(blockIdx.x / nblk);
-    const int64_t range = slab_fastest ? blockIdx.x / nslab : blockIdx.x % nblk;
+    const int slab = (int)(blockIdx.x % nslab);
+    const int64_t range = blockIdx.x / nslab;
     const int m = slab / fblocks;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, col = lane & 31;
@@ -390,8 +390,8 @@ __device__ __forceinline__ float bf16_value(uint32_t b) { return __uint_as_float
 template <int KSTEPS, bool PAIRED>     // ceil(d / 16): channels padded to 16*KSTEPS; PAIRED as in the fp32 kernel
 __global__ __launch_bounds__(256) void rff_increments_mfma_bf16(
     const float *__restrict__ X, const float *__restrict__ W, const float *__restrict__ sign, float inv_lengthscale,
-    float scale, int64_t rows, int64_t L, int64_t Lp, int d, int M, int F, int64_t rows_per_block, int64_t nblk,
-    int slab_fastest, float *__restrict__ dphi)
+    float scale, int64_t rows, int64_t L, int64_t Lp, int d, int M, int F, int64_t rows_per_block,
+    float *__restrict__ dphi)
 {
     constexpr int KP = 16 * KSTEPS;
     constexpr int XS = KP + 8;                  // bf16 elements per LDS row (16-byte padded)
@@ -399,8 +399,8 @@ __global__ __launch_bounds__(256) void rff_increments_mfma_bf16(
     __shared__ __attribute__((aligned(16))) uint16_t xlo[2 * kRowsPerTile * XS];
     const int fblocks = (F + 127) / 128;                              // same block order as the fp32 kernel
     const int nslab = M * fblocks;
-    const int slab = slab_fastest ? (int)(blockIdx.x % nslab) : (int)(blockIdx.x / nblk);
-    const int64_t range = slab_fastest ? blockIdx.x / nslab : blockIdx.x % nblk;
+    const int slab = (int)(blockIdx.x % nslab);
+    const int64_t range = blockIdx.x / nslab;
     const int m = slab / fblocks;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, col = lane & 31;
@@ -511,7 +511,6 @@ hipError_t launch_rff_increments(const float *X, const float *W, const float *si
     const int64_t nblk = paired ? (rows - 2) / rows_per_block + 1 : (rows - 1 + rows_per_block - 1) / rows_per_block;
     const float scale = 0.5f / sqrtf((float)F);    // the consumer's two-for-one FFT wants halved increments
     if (nblk * M * ((F + 127) / 128) > 0x7fffffffLL) return hipErrorInvalidValue;
-    const int slab_fastest = M * ((F + 127) / 128) >= 8;
     if (bf16) {            // the caller (API layer) has checked d <= 128
         const int fb = (F + 127) / 128;
         dim3 grid((unsigned)(nblk * M * fb));
@@ -519,12 +518,10 @@ hipError_t launch_rff_increments(const float *X, const float *W, const float *si
     do {                                                                                                         \
         if (paired)                                                                                              \
             hipLaunchKernelGGL((rff_increments_mfma_bf16<KS, true>), grid, dim3(256), 0, stream, X, W, sign,     \
-                               inv_lengthscale, scale, rows, L, Lp, d, M, F, rows_per_block, nblk, slab_fastest, \
-                               dphi);                                                                            \
+                               inv_lengthscale, scale, rows, L, Lp, d, M, F, rows_per_block, dphi);              \
         else                                                                                                     \
             hipLaunchKernelGGL((rff_increments_mfma_bf16<KS, false>), grid, dim3(256), 0, stream, X, W, sign,    \
-                               inv_lengthscale, scale, rows, L, Lp, d, M, F, rows_per_block, nblk, slab_fastest, \
-                               dphi);                                                                            \
+                               inv_lengthscale, scale, rows, L, Lp, d, M, F, rows_per_block, dphi);              \
     } while (0)
         if (d <= 16) RFSF_LAUNCH_BF16(1);
         else if (d <= 32) RFSF_LAUNCH_BF16(2);
@@ -540,12 +537,10 @@ hipError_t launch_rff_increments(const float *X, const float *W, const float *si
     do {                                                                                                         \
         if (paired)                                                                                              \
             hipLaunchKernelGGL((rff_increments_mfma<KS, true>), grid, dim3(256), 0, stream, X, W, sign,          \
-                               inv_lengthscale, scale, rows, L, Lp, d, M, F, rows_per_block, nblk, slab_fastest, \
-                               dphi);                                                                            \
+                               inv_lengthscale, scale, rows, L, Lp, d, M, F, rows_per_block, dphi);              \
         else                                                                                                     \
             hipLaunchKernelGGL((rff_increments_mfma<KS, false>), grid, dim3(256), 0, stream, X, W, sign,         \
-                               inv_lengthscale, scale, rows, L, Lp, d, M, F, rows_per_block, nblk, slab_fastest, \
-                               dphi);                                                                            \
+                               inv_lengthscale, scale, rows, L, Lp, d, M, F, rows_per_block, dphi);              \
     } while (0)
         if (d <= 4) RFSF_LAUNCH_MFMA(2);
         else if (d <= 8) RFSF_LAUNCH_MFMA(4);
