@@ -466,3 +466,29 @@ def test_variable_length_batches(oracle, N, L, d, M, F, D, order):
                                  lengths=bad).cpu().numpy()
     full = oracle.features(inp["X"], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D, order=order)
     assert np.all(got2[:2, 1:] == 0.0) and np.all(block_errors(got2[2:], full[2:], M, D) <= FP32_BLOCK_TOL)
+
+
+@pytest.mark.parametrize("N,L,d,M,F", [
+    (300, 1000, 3, 2, 128),     # 2364 workgroups of eight tiles: the projection kernel takes row ranges of four tiles
+    (301, 999, 3, 2, 100),      # the same with an odd sequence length (padded row space) and a partly used slab
+    (5000, 100, 4, 1, 100),     # 1969 workgroups of eight tiles: ranges of two tiles over many short sequences
+])
+def test_projection_row_ranges_between_the_small_and_the_large_problems(oracle, N, L, d, M, F):
+    """The projection kernel cuts the rows into ranges of 62, 126 or 254 increments by the size of the problem;
+    the small test shapes only see the first and the full-size ones the last. Rows at both ends, at range
+    boundaries and in the middle against the oracle."""
+    D = 64
+    inp = _random_case(N + L, N, L, d, M, F, D, step=0.05)
+    got = _gpu_features(inp, D).cpu().numpy()
+    sel = np.unique(np.array([0, 1, N // 7, N // 2, N // 2 + 1, N - 2, N - 1] +
+                             [min(N - 1, (126 * k) // (L - 1)) for k in (1, 2, 3, 50, 777)]))
+    want = oracle.features(inp["X"][sel], inp["W"], inp["hash"], inp["sign"], inp["lengthscale"], D)
+    err = block_errors(got[sel], want, M, D)
+    assert np.all(err <= FP32_BLOCK_TOL), err
+    # every row: level 1 telescopes to the sketch of phi(x_L) - phi(x_1), so its buckets sum to the signed sum of
+    # that difference; a row written to the wrong place or skipped shows up here
+    lvl1 = got[:, 1:1 + D].sum(axis=1)
+    X, W, sign, ls = inp["X"].astype(np.float64), inp["W"].astype(np.float64), inp["sign"].astype(np.float64), inp["lengthscale"]
+    th1, th0 = X[:, -1] @ W[0] / ls, X[:, 0] @ W[0] / ls
+    dphi = np.concatenate([np.cos(th1) - np.cos(th0), np.sin(th1) - np.sin(th0)], axis=1) / np.sqrt(F)
+    np.testing.assert_allclose(lvl1, dphi @ sign[0], atol=2e-4)
