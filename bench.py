@@ -32,8 +32,9 @@ MFMA_FP32_PEAK_TFLOPS = 157.3    # MI355X dense fp32 matrix, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix, published
 
 
-VALU_FP32_UNPACKED_TFLOPS = 78.6  # fp32 vector without packed instructions (157.3 with): one fused multiply-add per lane
-                                  # and cycle on 256 CUs x 64 lanes at 2.4 GHz, the rate this library's code can reach
+VALU_FP32_PEAK_TFLOPS = 157.3     # MI355X fp32 vector, published: 256 CUs x 128 fused multiply-adds per clock at 2.4 GHz. A loop of
+                                  # plain (unpacked) v_fma_f32 chains measures 118 TFLOP/s here (rfsf_ts_probe_peaks), so the
+                                  # rate does not hinge on packed instructions, which this library is built without
 COS_FLOPS = 20                   # argument (fma), reduction by pi (fma, sub, 2 fma), r^2, degree-5 polynomial in r^2 (5 fma)
 
 
@@ -80,16 +81,16 @@ def bench_dp1d(args, w, inp, dev, ls) -> int:
     ms = prof["ms_dp1d"] / max(1, prof["launches_dp1d"])
     valu_tflops = elements * (COS_FLOPS + 3.0) / (ms * 1e-3) / 1e12
     mfma_tflops = elements * 2.0 * w.d / (ms * 1e-3) / 1e12
-    valu_frac, mfma_frac = valu_tflops / VALU_FP32_UNPACKED_TFLOPS, mfma_tflops / MFMA_FP32_PEAK_TFLOPS
+    valu_frac, mfma_frac = valu_tflops / VALU_FP32_PEAK_TFLOPS, mfma_tflops / MFMA_FP32_PEAK_TFLOPS
     gram_pairs = w.N * w.N if ((w.N + 63) // 64) * ((w.N + 63) // 64 + 1) // 2 < 512 else w.N * (w.N + 1) / 2
     gms = prof["ms_gram"] / max(1, prof["launches_gram"])
     by_mfma = mfma_frac > valu_frac
     kernels = {
         "dp1d": {"bound": "mfma" if by_mfma else "alu", "achieved": mfma_tflops if by_mfma else valu_tflops,
-                 "peak": MFMA_FP32_PEAK_TFLOPS if by_mfma else VALU_FP32_UNPACKED_TFLOPS, "unit": "TFLOP/s",
+                 "peak": MFMA_FP32_PEAK_TFLOPS if by_mfma else VALU_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
                  "frac": max(mfma_frac, valu_frac), "traffic": None, "avg_launch_ms": ms,
                  "ms_per_step": prof["ms_dp1d"] / args.steps,
-                 "alu_frac": valu_frac, "alu_peak": VALU_FP32_UNPACKED_TFLOPS, "mfma_frac": mfma_frac,
+                 "alu_frac": valu_frac, "alu_peak": VALU_FP32_PEAK_TFLOPS, "mfma_frac": mfma_frac,
                  "cosines_per_s": elements / (ms * 1e-3)},
         "gram": {"bound": "mfma", "achieved": 2.0 * gram_pairs * ncols / (gms * 1e-3) / 1e12,
                  "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -107,6 +108,8 @@ def bench_dp1d(args, w, inp, dev, ls) -> int:
                    "lengthscale": ls, "paths": w.kind, "step": "DP-1D features + Gram"},
         "roofline": roofline, "kernels": kernels,
     }
+    if getattr(args, "measured_peaks", None):
+        result["measured_peaks"] = dict(args.measured_peaks)
     if not args.no_cpu_baseline:
         import oracle
         from tests.parity import block_errors
@@ -191,6 +194,8 @@ def bench_trp(args, w, inp, dev, ls) -> int:
                    "lengthscale": ls, "paths": w.kind, "step": "TRP features + Gram", "workspace_bytes": rec},
         "roofline": roofline, "kernels": kernels,
     }
+    if getattr(args, "measured_peaks", None):
+        result["measured_peaks"] = dict(args.measured_peaks)
     if not args.no_cpu_baseline:
         import oracle
         from tests.parity import block_errors
@@ -342,8 +347,19 @@ def bench_ts(args, name: str, steps: int, warmup: int, cpu_baseline: bool) -> di
     gram_pairs = w.N * Ny if (w.N2 or ((w.N + 63) // 64) * ((w.N + 63) // 64 + 1) // 2 < 512) else w.N * (w.N + 1) / 2
     entry("gram", "mfma", 2.0 * gram_pairs * w.ncols, "TFLOP/s", MFMA_FP32_PEAK_TFLOPS)
     entry("normalize", "hbm", 2.0 * 4.0 * n_seq * w.ncols, "GB/s", HBM_PEAK_GBS)
+    # beside the published peaks: what the simplest kernels of the same kind reach on this GPU (streaming reads for
+    # the kernel that reads the increments, non-temporal streaming writes for the one that writes them, an issue
+    # loop of fp32 matrix instructions for the Gram)
+    peaks = getattr(args, "measured_peaks", None)
+    if peaks:
+        for kname, key in (("rff_increments", "write_nt_gbs"), ("sketch_fft_scan", "read_gbs"), ("gram", "mfma_f32_tflops"),
+                           ("normalize", "copy_gbs")):
+            if kname in kernels:
+                kernels[kname]["measured_peak"] = peaks[key]
+                kernels[kname]["frac_of_measured"] = kernels[kname]["achieved"] / peaks[key]
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
-    roofline = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
+    roofline = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic",
+                                                   "measured_peak", "frac_of_measured") if k in kernels[dominant]}
     roofline["kernel"] = dominant
 
     result = {
@@ -412,6 +428,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default: 50 / 3 / 1)")
     ap.add_argument("--workload", default="medium", choices=["tiny", "small", "medium", "long", "large", "paper", "paper_long"],
                     help="medium (default) is the largest configuration that runs in fp32 throughout")
+    ap.add_argument("--no-measured-peaks", action="store_true",
+                    help="skip the probe of what plain streaming kernels and issue loops reach on this GPU")
     ap.add_argument("--also", default=None,
                     help="comma-separated further workloads measured after the headline one with their own default "
                          "step counts and reported under 'other_workloads' (default: small,long,large,paper,paper_long when the "
@@ -449,6 +467,12 @@ def main() -> int:
     from paper_2501_07145_amd import workloads as wl
 
     torch.cuda.set_device(0)
+    if not args.no_measured_peaks:
+        import paper_2501_07145_amd as rfsf
+        scratch = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")      # 16 times the last-level cache
+        args.measured_peaks = rfsf.rfsf_ts_probe_peaks(scratch)
+        del scratch
+        torch.cuda.empty_cache()
     if args.variant != "ts":
         w = wl.WORKLOADS[args.workload]
         inp = wl.make_inputs(w, 0)
@@ -458,6 +482,9 @@ def main() -> int:
         return bench_trp(args, w, inp, dev, inp["lengthscale"])
 
     result = bench_ts(args, args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    if getattr(args, "measured_peaks", None):
+        result["measured_peaks"] = dict(args.measured_peaks, note="plain streaming kernels over 4 GiB and fp32 issue loops, "
+                                        "measured at the start of this run (rfsf_ts_probe_peaks)")
     others = [n for n in args.also.split(",") if n and n != "none" and n != args.workload]
     if others:
         # the other configurations, each at its own default step count, without the oracle leg: context for the
@@ -472,7 +499,7 @@ def main() -> int:
                 "value": r["value"], "ms_per_step": r["ms_per_step"], "steps": r["steps"], "dtype": r["dtype"],
                 "config": r["config"],
                 "kernels": {k: {f: v[f] for f in ("bound", "frac", "achieved", "unit", "avg_launch_ms",
-                                                   "launches_per_step") if f in v}
+                                                   "launches_per_step", "frac_of_measured") if f in v}
                             for k, v in r["kernels"].items()}}
     print(json.dumps(result))
     return 0

@@ -269,6 +269,20 @@ typedef struct {
 int rfsf_ts_profile_enable(int on);
 int rfsf_ts_profile_read(rfsf_ts_profile *out, int reset);
 
+/*
+ * Benchmark helper (not part of the method): what this GPU gives the simplest kernels of each kind --
+ * streaming reads, writes with plain and with non-temporal stores and a copy over `scratch` (device memory,
+ * contents destroyed, at least 64 bytes; make it much larger than the 256 MB last-level cache), an issue
+ * loop of fp32 matrix instructions (v_mfma_f32_32x32x2f32) and one of fp32 fused multiply-adds. GB/s count
+ * bytes read plus bytes written, TFLOP/s two flop per multiply-add. Enqueues on `hip_stream` and waits for
+ * it. bench.py prints these beside the published peaks its roofline fractions are quoted against.
+ */
+typedef struct {
+    double read_gbs, write_gbs, write_nt_gbs, copy_gbs;   /* HBM streams */
+    double mfma_f32_tflops, valu_f32_tflops;              /* issue loops */
+} rfsf_ts_peaks;
+int rfsf_ts_probe_peaks(void *scratch, size_t scratch_bytes, rfsf_ts_peaks *out, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -40,6 +40,11 @@ class _Profile(ctypes.Structure):
                 ("ms_trp_scan", ctypes.c_double), ("launches_trp_scan", ctypes.c_int64)]
 
 
+class _Peaks(ctypes.Structure):
+    _fields_ = [("read_gbs", ctypes.c_double), ("write_gbs", ctypes.c_double), ("write_nt_gbs", ctypes.c_double),
+                ("copy_gbs", ctypes.c_double), ("mfma_f32_tflops", ctypes.c_double), ("valu_f32_tflops", ctypes.c_double)]
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -80,6 +85,8 @@ def load_library():
     lib.rfsf_trp_features.argtypes = [ctypes.POINTER(_Shape), vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
     lib.rfsf_ts_profile_enable.restype = ctypes.c_int
     lib.rfsf_ts_profile_enable.argtypes = [ctypes.c_int]
+    lib.rfsf_ts_probe_peaks.restype = ctypes.c_int
+    lib.rfsf_ts_probe_peaks.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(_Peaks), ctypes.c_void_p]
     lib.rfsf_ts_profile_read.restype = ctypes.c_int
     lib.rfsf_ts_profile_read.argtypes = [ctypes.POINTER(_Profile), ctypes.c_int]
     _lib = lib
@@ -323,6 +330,17 @@ def rfsf_ts_gram(PhiX: torch.Tensor, PhiY: Optional[torch.Tensor] = None,
 
 def rfsf_ts_profile_enable(on: bool) -> None:
     _check(load_library().rfsf_ts_profile_enable(int(bool(on))))
+
+
+def rfsf_ts_probe_peaks(scratch: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> dict:
+    """What the GPU gives plain streaming kernels (GB/s) and fp32 issue loops (TFLOP/s); `scratch` is any
+    contiguous device tensor, its contents are destroyed."""
+    if not scratch.is_cuda or not scratch.is_contiguous():
+        raise ValueError("scratch must be a contiguous device tensor")
+    p = _Peaks()
+    _check(load_library().rfsf_ts_probe_peaks(ctypes.c_void_p(scratch.data_ptr()), scratch.numel() * scratch.element_size(),
+                                              ctypes.byref(p), ctypes.c_void_p(_stream_ptr(stream))))
+    return {f: getattr(p, f) for f, _ in _Peaks._fields_}
 
 
 def rfsf_ts_profile_read(reset: bool = True) -> dict:

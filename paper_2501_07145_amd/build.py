@@ -8,7 +8,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "librfsf_ts.so")
-SOURCES = ["rfsf_ts_api.hip", "rff_increments.hip", "sketch_fft_scan.hip", "gram.hip", "normalize.hip", "dp1d.hip", "trp.hip", "join_pieces.hip"] + \
+SOURCES = ["rfsf_ts_api.hip", "rff_increments.hip", "sketch_fft_scan.hip", "gram.hip", "normalize.hip", "dp1d.hip", "trp.hip", "join_pieces.hip", "probe.hip"] + \
     [f"sketch_fft_scan_d{n}.hip" for n in [6, 7, 8, 9, 10, 12, 13, 100, 200, 500, 1000, 2048]]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -82,6 +82,9 @@ hipError_t launch_trp_scan(const float *P, int64_t n_seq, int64_t L, int M, int 
 
 hipError_t launch_normalize(float *Phi, int64_t N, int64_t ld, int M, int D, hipStream_t stream);
 
+// Benchmark helper (csrc/probe.hip): read, write, non-temporal write, copy GB/s over `scratch`, fp32 matrix and
+// fp32 vector TFLOP/s of issue loops, in this order; waits for the stream.
+hipError_t probe_peaks(void *scratch, size_t bytes, double out[6], hipStream_t stream);
 hipError_t launch_validate_tables(const int32_t *hash, const float *sign, int64_t count, int D,
                                   int *flag, hipStream_t stream);
 

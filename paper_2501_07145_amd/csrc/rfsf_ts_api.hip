@@ -577,6 +577,16 @@ extern "C" int rfsf_trp_features(const rfsf_ts_shape *shape, const float *X, con
     return RFSF_OK;
 }
 
+extern "C" int rfsf_ts_probe_peaks(void *scratch, size_t scratch_bytes, rfsf_ts_peaks *out, void *hip_stream)
+{
+    if (!scratch || !out) return RFSF_E_NULLPTR;
+    if (scratch_bytes < 64) return RFSF_E_WORKSPACE_TOO_SMALL;
+    double v[6];
+    if (rfsf::probe_peaks(scratch, scratch_bytes, v, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return RFSF_E_HIP;
+    *out = rfsf_ts_peaks{v[0], v[1], v[2], v[3], v[4], v[5]};
+    return RFSF_OK;
+}
+
 extern "C" int rfsf_ts_profile_enable(int on)
 {
     rfsf::g_profile_on = on != 0;

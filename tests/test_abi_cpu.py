@@ -164,3 +164,12 @@ def test_time_cut_plan_is_a_function_of_the_shape():
     rec, mn = binding.rfsf_ts_workspace_bytes(10, 100000, 5, 5, 50, 100)
     rec1, mn1 = binding.rfsf_ts_workspace_bytes(65, 100000, 5, 5, 50, 100)
     assert rec / 10 > rec1 / 65 and mn > mn1 and rec >= mn
+
+
+def test_probe_peaks_refuses_bad_arguments():
+    import ctypes
+    lib = binding.load_library()
+    out = binding._Peaks()
+    assert lib.rfsf_ts_probe_peaks(None, 1 << 20, ctypes.byref(out), None) == -1           # no scratch
+    assert lib.rfsf_ts_probe_peaks(ctypes.c_void_p(64), 1 << 20, None, None) == -1         # nowhere to write to
+    assert lib.rfsf_ts_probe_peaks(ctypes.c_void_p(64), 8, ctypes.byref(out), None) == -6  # too small
